@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Throughput benchmark of the PR-SGD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--interval I]
+
+A step is one iteration of Algorithm 1 over all N workers: seeded minibatch draw, forward,
+backward, local update (eq. 3), plus the restart average (eq. 2) after every I-th
+iteration.  Inputs are synthetic and resident in HBM before the timed region.  Prints ONE JSON
+line: samples/s over the N replicas, a roofline record for the kernel that dominates the
+step, the restart-average bandwidth, and the CPU oracle timed on a bounded sample of the same
+workload as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+# rocprofv3 kernel symbol behind each timing label of the library
+KERNEL_SYMBOL = {
+    "gather": "gather_kernel", "gemm_fwd": "grouped_gemm_kernel<.., OP_CONTIG, OP_TRANS>",
+    "gemm_dx": "grouped_gemm_kernel<.., OP_CONTIG, OP_CONTIG>",
+    "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>", "softmax_xent": "softmax_xent_kernel",
+    "sgd_update": "update_kernel", "average": "average_kernel", "lsq_steps": "lsq_steps_kernel",
+}
+
+
+def algorithmic_work(w):
+    """Algorithmic HBM bytes and flops of ONE iteration, per kernel label (all launches of
+    that label in the iteration summed), plus those of one restart average."""
+    n, b = w.n_workers, w.batch
+    out = {}
+    if w.model == "lsq":
+        d = w.dims[0]
+        out["lsq_steps"] = {"bytes": n * b * (d + 1) * 4, "flops": 4 * n * b * d}
+        out["average"] = {"bytes": 8 * n * d, "flops": n * d}
+        return out
+    es = 2 if w.gemm_dtype == "bf16" else 4          # operand element size
+    dims = w.dims
+    layers = [(dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
+    m = sum(di * do + do for di, do in layers)
+    pw = sum(di * do for di, do in layers)
+    shadow = 2 if w.gemm_dtype == "bf16" else 0
+    fwd_b = sum(n * (di * do * es + b * di * es + b * do * es) for di, do in layers)
+    fwd_f = sum(2 * n * b * di * do for di, do in layers)
+    dx_b = sum(n * (di * do * es + b * do * es + 2 * b * di * es) for di, do in layers[1:])
+    dx_f = sum(2 * n * b * di * do for di, do in layers[1:])
+    dw_b = sum(n * (di * do * (8 + shadow) + b * (di + do) * es) for di, do in layers)
+    dw_f = fwd_f
+    out["gather"] = {"bytes": n * b * dims[0] * (4 + es), "flops": 0}
+    out["gemm_fwd"] = {"bytes": fwd_b, "flops": fwd_f}
+    out["gemm_dx"] = {"bytes": dx_b, "flops": dx_f}
+    out["gemm_dw"] = {"bytes": dw_b, "flops": dw_f}
+    out["softmax_xent"] = {"bytes": n * b * dims[-1] * (4 + es), "flops": 0}
+    out["sgd_update"] = {"bytes": n * m * (12 + shadow), "flops": 2 * n * m}
+    out["average"] = {"bytes": n * m * 8 + n * pw * shadow, "flops": n * m}
+    return out
+
+
+def cpu_baseline(w, inp, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores on a bounded number of iterations."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    args = dict(model=w.model, dims=w.dims, activation=w.activation, features=inp["features"],
+                targets=inp["targets"], x0=inp["x0"], n_workers=w.n_workers, batch=w.batch,
+                lr=w.lr, interval=w.interval, seed=w.index_seed, bf16=(w.gemm_dtype == "bf16"))
+    t0 = time.perf_counter()
+    oracle.run_prsgd(iterations=1, **args)
+    t_one = time.perf_counter() - t0
+    iters = int(max(1, min(w.iterations, budget_s / max(t_one, 1e-6))))
+    t0 = time.perf_counter()
+    oracle.run_prsgd(iterations=iters, **args)
+    dt = time.perf_counter() - t0
+    return {"value": w.n_workers * w.batch * iters / dt, "unit": "samples/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": "%d iterations of workload %s (incl. %d restart averages), %.1f s, numpy float64"
+                      % (iters, w.name, iters // w.interval, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--interval", type=int, default=None)
+    ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rows", type=int, default=None, help="rows per worker (default: workload's)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the N workers are simulated on it); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    if not os.path.exists(os.path.join(ROOT, "paper_1807_06629_amd", "libprsgd.so")):
+        from paper_1807_06629_amd.build import build
+        build()
+    from paper_1807_06629_amd import drivers, prsgd
+    from workloads import get_workload, make_inputs
+
+    w = get_workload(args.workload)
+    if args.interval is not None:
+        w = w.scaled(interval=args.interval)
+    if args.rows is not None:
+        w = w.scaled(rows_per_worker=args.rows)
+    steps = args.steps if args.steps is not None else min(w.iterations, 2000)
+    warmup = args.warmup if args.warmup is not None else 2 * w.interval
+
+    inp = make_inputs(w)
+    stream = torch.cuda.Stream(device="cuda:0")
+    with torch.cuda.stream(stream):
+        h = drivers.open_workload(w, inp, device="cuda:0", fused_update=not args.unfused,
+                                  stream=stream)
+    torch.cuda.synchronize()
+
+    prsgd.prsgd_run(h, warmup, w.interval)
+    prsgd.prsgd_set_iteration(h, 0)                  # timed region starts on an epoch boundary
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    prsgd.prsgd_run(h, steps, w.interval)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    loss = float(prsgd.prsgd_read_loss(h).mean())
+
+    # per-kernel durations: the same steps again with every launch bracketed by HIP events on
+    # the library's stream
+    prof_steps = min(steps, max(2 * w.interval, 64))
+    prsgd.prsgd_set_iteration(h, 0)
+    prsgd.prsgd_profile_enable(h, True)
+    prsgd.prsgd_run(h, prof_steps, w.interval)
+    stats = prsgd.prsgd_profile_read(h)
+    prsgd.prsgd_profile_enable(h, False)
+
+    work = algorithmic_work(w)
+    kernels = {}
+    for s in stats:
+        per_iter = work.get(s["name"], {"bytes": 0, "flops": 0})
+        calls = prof_steps if s["name"] != "average" else max(1, prof_steps // w.interval)
+        if w.model == "lsq" and s["name"] == "lsq_steps":
+            calls = prof_steps                        # one launch covers several iterations
+        tot_bytes, tot_flops = per_iter["bytes"] * calls, per_iter["flops"] * calls
+        sec = s["total_ms"] * 1e-3
+        kernels[s["name"]] = {
+            "launches": s["launches"], "avg_us": 1e3 * s["total_ms"] / s["launches"],
+            "total_ms": s["total_ms"], "GBps": tot_bytes / sec / 1e9 if sec > 0 else None,
+            "TFLOPs": tot_flops / sec / 1e12 if sec > 0 else None,
+            "bytes_per_launch": tot_bytes / s["launches"], "flops_per_launch": tot_flops / s["launches"],
+        }
+    dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
+    kd = kernels[dom]
+    peak_tf = MFMA_PEAK_TFLOPS[w.gemm_dtype if w.model == "mlp" else "f32"]
+    t_hbm = kd["bytes_per_launch"] / (HBM_PEAK_GBPS * 1e9)
+    t_mfma = kd["flops_per_launch"] / (peak_tf * 1e12)
+    if t_hbm >= t_mfma:
+        roof = {"bound": "hbm", "achieved": kd["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": kd["GBps"] / HBM_PEAK_GBPS}
+    else:
+        roof = {"bound": "mfma", "achieved": kd["TFLOPs"], "peak": peak_tf, "unit": "TFLOP/s",
+                "frac": kd["TFLOPs"] / peak_tf}
+    roof.update({"traffic": None, "kernel": dom, "symbol": KERNEL_SYMBOL.get(dom, dom),
+                 "avg_launch_us": kd["avg_us"], "launches_timed": kd["launches"],
+                 "algorithmic_bytes_per_launch": kd["bytes_per_launch"],
+                 "algorithmic_flops_per_launch": kd["flops_per_launch"]})
+
+    avg = kernels.get("average")
+    restart = None
+    if avg:
+        restart = {"GBps": avg["GBps"], "frac_of_hbm_peak": avg["GBps"] / HBM_PEAK_GBPS,
+                   "avg_us": avg["avg_us"], "bytes": avg["bytes_per_launch"]}
+
+    out = {
+        "metric": "samples/sec across N replicas at interval I; restart-average HBM GB/s",
+        "value": w.n_workers * w.batch * steps / wall,
+        "unit": "samples/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * wall / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if (w.model == "mlp" and w.gemm_dtype == "bf16") else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s %s N=%d B=%d I=%d n=%d lr=%g %s" % (
+            w.name, w.model, "-".join(str(d) for d in w.dims), w.n_workers, w.batch, w.interval,
+            w.rows_per_worker, w.lr, w.activation),
+            "n_workers": w.n_workers, "batch": w.batch, "interval": w.interval,
+            "fused_update": not args.unfused, "last_minibatch_loss": loss},
+        "roofline": roof,
+        "restart_average": restart,
+        "kernels": {k: {"avg_us": round(v["avg_us"], 3), "launches": v["launches"],
+                        "GBps": v["GBps"], "TFLOPs": v["TFLOPs"]} for k, v in kernels.items()},
+    }
+    prsgd.prsgd_destroy(h)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

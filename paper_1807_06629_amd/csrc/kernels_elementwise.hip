@@ -1,0 +1,209 @@
+// Bandwidth-bound kernels over the replica-batched parameter buffer [N][m_pad]:
+//   restart average   ybar = (1/N) sum_i x_i, then x_i <- ybar for every i   (Algorithm 1, eq. 2)
+//   node average      xbar of eq. (4) into a separate vector (read-out, replicas untouched)
+//   local update      x <- x - gamma g                                       (Algorithm 1, eq. 3)
+// The reduction runs across replicas, not across lanes: a thread owns one 16-byte column of the
+// buffer, streams the N replica values through registers in ascending worker order (a fixed,
+// run-to-run deterministic summation order) and writes the mean back N times.  Every global
+// access is a fully coalesced 16-byte vector, so the kernels need neither LDS nor cross-lane
+// traffic and are limited by HBM alone.
+#include "prsgd_internal.h"
+
+namespace prsgd {
+
+constexpr int kChunk = 8;   // replica loads kept in flight per thread
+
+__device__ __forceinline__ float4 add4(float4 a, float4 b) {
+  return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+}
+__device__ __forceinline__ uint2 pack_bf16x4(float4 v) {
+  uint2 r;
+  r.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
+  r.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
+  return r;
+}
+
+// Sum of column `col` (float4 index) over the replicas, ascending i.
+__device__ __forceinline__ float4 replica_sum(const float4* __restrict__ p, size_t stride4, size_t col,
+                                              int n) {
+  float4 s = p[col];
+  int i = 1;
+  for (; i + kChunk <= n; i += kChunk) {
+    float4 v[kChunk];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) v[u] = p[(size_t)(i + u) * stride4 + col];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) s = add4(s, v[u]);
+  }
+  for (; i < n; ++i) s = add4(s, p[(size_t)i * stride4 + col]);
+  return s;
+}
+
+template <bool SHADOW>
+__global__ __launch_bounds__(kThreads) void average_kernel(float4* __restrict__ params,
+                                                           uint2* __restrict__ shadow, size_t stride4,
+                                                           int n, float n_f) {
+  for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
+       col += (size_t)gridDim.x * kThreads) {
+    const float4 s = replica_sum(params, stride4, col, n);
+    const float4 mean = make_float4(s.x / n_f, s.y / n_f, s.z / n_f, s.w / n_f);
+    for (int i = 0; i < n; ++i) params[(size_t)i * stride4 + col] = mean;
+    if (SHADOW) {
+      const uint2 h = pack_bf16x4(mean);
+      for (int i = 0; i < n; ++i) shadow[(size_t)i * stride4 + col] = h;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void mean_kernel(const float4* __restrict__ params,
+                                                        float4* __restrict__ out, size_t stride4, int n,
+                                                        float n_f) {
+  for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
+       col += (size_t)gridDim.x * kThreads) {
+    const float4 s = replica_sum(params, stride4, col, n);
+    out[col] = make_float4(s.x / n_f, s.y / n_f, s.z / n_f, s.w / n_f);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void broadcast_kernel(const float4* __restrict__ src,
+                                                             float4* __restrict__ params,
+                                                             uint2* __restrict__ shadow, size_t stride4,
+                                                             int n) {
+  for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
+       col += (size_t)gridDim.x * kThreads) {
+    const float4 v = src[col];
+    for (int i = 0; i < n; ++i) params[(size_t)i * stride4 + col] = v;
+    if (shadow != nullptr) {
+      const uint2 h = pack_bf16x4(v);
+      for (int i = 0; i < n; ++i) shadow[(size_t)i * stride4 + col] = h;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void refresh_shadow_kernel(const float4* __restrict__ params,
+                                                                  uint2* __restrict__ shadow,
+                                                                  size_t count4) {
+  for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < count4;
+       k += (size_t)gridDim.x * kThreads)
+    shadow[k] = pack_bf16x4(params[k]);
+}
+
+// x <- x - lr * g on float4 columns; `tail` scalars at the end when count % 4 != 0.
+__global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ x,
+                                                          const float* __restrict__ g,
+                                                          uint16_t* __restrict__ shadow, size_t count,
+                                                          float lr) {
+  const size_t count4 = count / 4;
+  float4* x4 = reinterpret_cast<float4*>(x);
+  const float4* g4 = reinterpret_cast<const float4*>(g);
+  uint2* s4 = reinterpret_cast<uint2*>(shadow);
+  for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < count4;
+       k += (size_t)gridDim.x * kThreads) {
+    float4 xv = x4[k];
+    const float4 gv = g4[k];
+    xv.x = fmaf(-lr, gv.x, xv.x);
+    xv.y = fmaf(-lr, gv.y, xv.y);
+    xv.z = fmaf(-lr, gv.z, xv.z);
+    xv.w = fmaf(-lr, gv.w, xv.w);
+    x4[k] = xv;
+    if (shadow != nullptr) s4[k] = pack_bf16x4(xv);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (count & 3)) {
+    const size_t k = count4 * 4 + threadIdx.x;
+    const float xv = fmaf(-lr, g[k], x[k]);
+    x[k] = xv;
+    if (shadow != nullptr) shadow[k] = f32_to_bf16_rne(xv);
+  }
+}
+
+// Same update over [N][m_pad] with finished workers (Algorithm 3) left untouched.
+__global__ __launch_bounds__(kThreads) void update_masked_kernel(float4* __restrict__ x,
+                                                                 const float4* __restrict__ g,
+                                                                 uint2* __restrict__ shadow,
+                                                                 size_t stride4, float lr,
+                                                                 const int* __restrict__ worker_steps,
+                                                                 int step) {
+  const int i = blockIdx.y;
+  if (worker_steps != nullptr && step >= worker_steps[i]) return;
+  for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
+       col += (size_t)gridDim.x * kThreads) {
+    const size_t k = (size_t)i * stride4 + col;
+    float4 xv = x[k];
+    const float4 gv = g[k];
+    xv.x = fmaf(-lr, gv.x, xv.x);
+    xv.y = fmaf(-lr, gv.y, xv.y);
+    xv.z = fmaf(-lr, gv.z, xv.z);
+    xv.w = fmaf(-lr, gv.w, xv.w);
+    x[k] = xv;
+    if (shadow != nullptr) shadow[k] = pack_bf16x4(xv);
+  }
+}
+
+static int grid_for(size_t items, int max_blocks) {
+  size_t b = (items + kThreads - 1) / kThreads;
+  if (b < 1) b = 1;
+  if (b > (size_t)max_blocks) b = max_blocks;
+  return (int)b;
+}
+
+// 256 CUs x 8 resident workgroups: enough waves to cover HBM latency without a long tail.
+constexpr int kStreamBlocks = 256 * 8;
+
+hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, hipStream_t s) {
+  const size_t stride4 = (size_t)m_pad / 4;
+  const int grid = grid_for(stride4, kStreamBlocks);
+  if (shadow != nullptr)
+    hipLaunchKernelGGL(average_kernel<true>, dim3(grid), dim3(kThreads), 0, s,
+                       reinterpret_cast<float4*>(params), reinterpret_cast<uint2*>(shadow), stride4,
+                       n_workers, (float)n_workers);
+  else
+    hipLaunchKernelGGL(average_kernel<false>, dim3(grid), dim3(kThreads), 0, s,
+                       reinterpret_cast<float4*>(params), (uint2*)nullptr, stride4, n_workers,
+                       (float)n_workers);
+  return hipGetLastError();
+}
+
+hipError_t launch_mean(const float* params, float* out, long m_pad, int n_workers, hipStream_t s) {
+  const size_t stride4 = (size_t)m_pad / 4;
+  hipLaunchKernelGGL(mean_kernel, dim3(grid_for(stride4, kStreamBlocks)), dim3(kThreads), 0, s,
+                     reinterpret_cast<const float4*>(params), reinterpret_cast<float4*>(out), stride4,
+                     n_workers, (float)n_workers);
+  return hipGetLastError();
+}
+
+hipError_t launch_broadcast(const float* src, float* params, uint16_t* shadow, long m_pad,
+                            int n_workers, hipStream_t s) {
+  const size_t stride4 = (size_t)m_pad / 4;
+  hipLaunchKernelGGL(broadcast_kernel, dim3(grid_for(stride4, kStreamBlocks)), dim3(kThreads), 0, s,
+                     reinterpret_cast<const float4*>(src), reinterpret_cast<float4*>(params),
+                     reinterpret_cast<uint2*>(shadow), stride4, n_workers);
+  return hipGetLastError();
+}
+
+hipError_t launch_refresh_shadow(const float* params, uint16_t* shadow, long count, hipStream_t s) {
+  const size_t count4 = (size_t)count / 4;
+  hipLaunchKernelGGL(refresh_shadow_kernel, dim3(grid_for(count4, kStreamBlocks)), dim3(kThreads), 0,
+                     s, reinterpret_cast<const float4*>(params), reinterpret_cast<uint2*>(shadow),
+                     count4);
+  return hipGetLastError();
+}
+
+hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t count, float lr,
+                         hipStream_t s) {
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(update_kernel, dim3(grid_for(count / 4 + 1, kStreamBlocks)), dim3(kThreads), 0, s,
+                     x, g, shadow, count, lr);
+  return hipGetLastError();
+}
+
+hipError_t launch_update_masked(float* x, const float* g, uint16_t* shadow, long m_pad, int n_workers,
+                                float lr, const int* worker_steps, int step, hipStream_t s) {
+  const size_t stride4 = (size_t)m_pad / 4;
+  int gx = grid_for(stride4, kStreamBlocks / (n_workers < 8 ? n_workers : 8));
+  hipLaunchKernelGGL(update_masked_kernel, dim3(gx, n_workers), dim3(kThreads), 0, s,
+                     reinterpret_cast<float4*>(x), reinterpret_cast<const float4*>(g),
+                     reinterpret_cast<uint2*>(shadow), stride4, lr, worker_steps, step);
+  return hipGetLastError();
+}
+
+}  // namespace prsgd

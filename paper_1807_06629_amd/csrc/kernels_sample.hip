@@ -1,0 +1,145 @@
+// Minibatch draw zeta_i^t and the loss head of the MLP.
+//
+// Section 1 of the paper only requires unbiased stochastic gradients that are independent
+// across workers and iterations.  Here worker i draws B rows of its own shard uniformly with
+// replacement; slot j of iteration t is a pure function of (seed, i, t, j) through
+// Philox4x32-10, so the stream needs no state and can be replayed from any t.
+#include "prsgd_internal.h"
+
+namespace prsgd {
+
+static int ilog2(long n) {
+  int l = 0;
+  while ((1L << l) < n) ++l;
+  return l;
+}
+
+// One workgroup per (slot j, worker i): draw the row, copy it into the batch buffer.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void gather_kernel(
+    const float* __restrict__ features, const int32_t* __restrict__ labels, void* __restrict__ xb,
+    int32_t* __restrict__ yb, int32_t* __restrict__ idx, int batch, int d0, int ld0, long rows,
+    int log2n, uint64_t seed, uint64_t t, const int* __restrict__ worker_steps, int step) {
+  const int j = blockIdx.x, i = blockIdx.y;
+  if (worker_steps != nullptr && step >= worker_steps[i]) return;
+  const int32_t row = sample_row(seed, (uint32_t)i, t, (uint32_t)j, log2n);
+  const size_t slot = (size_t)i * batch + j;
+  if (threadIdx.x == 0) {
+    idx[slot] = row;
+    yb[slot] = labels[(size_t)i * rows + row];
+  }
+  const float* src = features + ((size_t)i * rows + row) * d0;
+  if ((d0 & 3) == 0) {
+    const float4* src4 = reinterpret_cast<const float4*>(src);
+    for (int c = threadIdx.x; c < d0 / 4; c += kThreads) {
+      const float4 v = src4[c];
+      if (BF16) {
+        uint2 h;
+        h.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
+        h.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
+        reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(xb) + slot * ld0)[c] = h;
+      } else {
+        reinterpret_cast<float4*>(reinterpret_cast<float*>(xb) + slot * ld0)[c] = v;
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < d0; c += kThreads) {
+      if (BF16) reinterpret_cast<uint16_t*>(xb)[slot * ld0 + c] = f32_to_bf16_rne(src[c]);
+      else reinterpret_cast<float*>(xb)[slot * ld0 + c] = src[c];
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void sample_indices_kernel(int32_t* __restrict__ out,
+                                                                  int n_workers, int batch, int log2n,
+                                                                  uint64_t seed, uint64_t t_first,
+                                                                  size_t total) {
+  for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < total;
+       k += (size_t)gridDim.x * kThreads) {
+    const uint32_t j = (uint32_t)(k % batch);
+    const uint32_t i = (uint32_t)((k / batch) % n_workers);
+    const uint64_t s = k / ((size_t)batch * n_workers);
+    out[k] = sample_row(seed, i, t_first + s, j, log2n);
+  }
+}
+
+// Softmax cross-entropy head: one workgroup per worker, one wavefront per minibatch row.
+//   loss_i = -(1/B) sum_b log softmax(z_b)[c_b],   delta = (softmax(z) - onehot(c)) / B
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ yb, void* __restrict__ delta,
+    float* __restrict__ losses, int batch, int n_classes, int ldc,
+    const int* __restrict__ worker_steps, int step) {
+  const int g = blockIdx.x;
+  if (worker_steps != nullptr && step >= worker_steps[g]) return;
+  __shared__ float row_loss[kMaxBatch];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv_b = 1.0f / (float)batch;
+  for (int b = wave; b < batch; b += kThreads / kWave) {
+    const size_t r = (size_t)g * batch + b;
+    const float* z = logits + r * ldc;
+    float mx = -INFINITY;
+    for (int c = lane; c < n_classes; c += kWave) mx = fmaxf(mx, z[c]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float se = 0.0f;
+    for (int c = lane; c < n_classes; c += kWave) se += expf(z[c] - mx);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
+    const int label = yb[r];
+    for (int c = lane; c < ldc; c += kWave) {
+      float d = 0.0f;
+      if (c < n_classes) d = (expf(z[c] - mx) / se - (c == label ? 1.0f : 0.0f)) * inv_b;
+      if (BF16) reinterpret_cast<uint16_t*>(delta)[r * ldc + c] = f32_to_bf16_rne(d);
+      else reinterpret_cast<float*>(delta)[r * ldc + c] = d;
+    }
+    // an out-of-range label must not index outside the row
+    const float z_label = (label >= 0 && label < n_classes) ? z[label] : 0.0f;
+    if (lane == 0) row_loss[b] = (mx + logf(se)) - z_label;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.0f;
+    for (int b = 0; b < batch; ++b) s += row_loss[b];
+    losses[g] = s * inv_b;
+  }
+}
+
+hipError_t launch_gather(const float* features, const int32_t* labels, void* xb, int32_t* yb,
+                         int32_t* idx, int n_workers, int batch, int d0, int ld0, long rows,
+                         uint64_t seed, int64_t t, bool bf16, const int* worker_steps, int step,
+                         hipStream_t s) {
+  dim3 grid(batch, n_workers);
+  if (bf16)
+    hipLaunchKernelGGL(gather_kernel<true>, grid, dim3(kThreads), 0, s, features, labels, xb, yb, idx,
+                       batch, d0, ld0, rows, ilog2(rows), seed, (uint64_t)t, worker_steps, step);
+  else
+    hipLaunchKernelGGL(gather_kernel<false>, grid, dim3(kThreads), 0, s, features, labels, xb, yb, idx,
+                       batch, d0, ld0, rows, ilog2(rows), seed, (uint64_t)t, worker_steps, step);
+  return hipGetLastError();
+}
+
+hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long rows, int64_t t_first,
+                                 int n_steps, int32_t* out, hipStream_t s) {
+  const size_t total = (size_t)n_steps * n_workers * batch;
+  if (total == 0) return hipSuccess;
+  size_t blocks = (total + kThreads - 1) / kThreads;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(sample_indices_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, out,
+                     n_workers, batch, ilog2(rows), seed, (uint64_t)t_first, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* losses,
+                               int n_workers, int batch, int n_classes, int ldc, bool bf16,
+                               const int* worker_steps, int step, hipStream_t s) {
+  if (bf16)
+    hipLaunchKernelGGL(softmax_xent_kernel<true>, dim3(n_workers), dim3(kThreads), 0, s, logits, yb,
+                       delta, losses, batch, n_classes, ldc, worker_steps, step);
+  else
+    hipLaunchKernelGGL(softmax_xent_kernel<false>, dim3(n_workers), dim3(kThreads), 0, s, logits, yb,
+                       delta, losses, batch, n_classes, ldc, worker_steps, step);
+  return hipGetLastError();
+}
+
+}  // namespace prsgd

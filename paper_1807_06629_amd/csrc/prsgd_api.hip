@@ -1,0 +1,637 @@
+// C ABI of libprsgd: host-side driver of Algorithm 1 (and the epochs of Algorithms 2 and 3).
+// Only argument checking, buffer carving and kernel sequencing live here; every arithmetic
+// step of the method runs in the kernels.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "prsgd_internal.h"
+
+using namespace prsgd;
+
+namespace prsgd {
+const char* kernel_kind_name(int kind) {
+  static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
+                                        "sgd_update", "average", "mean",       "broadcast", "lsq_steps"};
+  return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
+}
+}  // namespace prsgd
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+thread_local char g_init_error[256] = "";
+
+struct Carve {
+  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, shadow = 0, grads = 0, mean = 0, steps = 0;
+  size_t h[PRSGD_MAX_DIMS] = {0}, delta[PRSGD_MAX_DIMS] = {0};
+  size_t total = 0;
+};
+
+bool build_layout(const prsgd_config* c, Layout* lo, char* err, size_t errn) {
+  auto fail = [&](const char* msg) { snprintf(err, errn, "%s", msg); return false; };
+  if (c == nullptr) return fail("config is null");
+  if (c->n_workers < 1 || c->n_workers > 65535) return fail("n_workers out of range");
+  if (c->batch < 1 || c->batch > kMaxBatch) return fail("batch out of range (1..4096)");
+  if (c->rows_per_worker < 1 || c->rows_per_worker > (1LL << 31) ||
+      (c->rows_per_worker & (c->rows_per_worker - 1)) != 0)
+    return fail("rows_per_worker must be a power of two");
+  if (!(c->lr == c->lr)) return fail("lr is NaN");
+  memset(lo, 0, sizeof(*lo));
+  if (c->model == PRSGD_LSQ) {
+    if (c->n_dims != 1) return fail("least squares takes n_dims == 1");
+    if (c->dims[0] < 1 || c->dims[0] > kMaxLsqDim) return fail("least-squares dimension out of range");
+    lo->n_layers = 0;
+    lo->d[0] = c->dims[0];
+    lo->ld[0] = c->dims[0];
+    lo->m = c->dims[0];
+    lo->m_pad = (long)align_up((size_t)c->dims[0], 64);
+    return true;
+  }
+  if (c->model != PRSGD_MLP) return fail("unknown model");
+  if (c->n_dims < 2 || c->n_dims > PRSGD_MAX_DIMS) return fail("an MLP takes 2..16 dims");
+  if (c->activation != PRSGD_TANH && c->activation != PRSGD_RELU) return fail("unknown activation");
+  if (c->gemm_dtype != PRSGD_F32 && c->gemm_dtype != PRSGD_BF16) return fail("unknown gemm_dtype");
+  lo->n_layers = c->n_dims - 1;
+  long off = 0, m = 0;
+  for (int l = 0; l < c->n_dims; ++l) {
+    if (c->dims[l] < 1 || c->dims[l] > (1 << 20)) return fail("layer width out of range");
+    lo->d[l] = c->dims[l];
+    lo->ld[l] = (int)align_up((size_t)c->dims[l], 8);
+  }
+  for (int l = 1; l < c->n_dims; ++l) {
+    lo->w_off[l - 1] = off;
+    off = (long)align_up((size_t)off + (size_t)lo->d[l - 1] * lo->ld[l], 64);
+    lo->b_off[l - 1] = off;
+    off = (long)align_up((size_t)off + (size_t)lo->ld[l], 64);
+    m += (long)lo->d[l - 1] * lo->d[l] + lo->d[l];
+  }
+  lo->m = m;
+  lo->m_pad = off;
+  return true;
+}
+
+void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kAlign); return o; };
+  const size_t n = (size_t)c->n_workers, b = (size_t)c->batch;
+  const bool bf16 = c->model == PRSGD_MLP && c->gemm_dtype == PRSGD_BF16;
+  const size_t es = bf16 ? 2 : 4;
+  cv->idx = take(n * b * 4);
+  cv->losses = take(n * 4);
+  cv->steps = take(n * 4);
+  cv->mean = take((size_t)lo.m_pad * 4);
+  if (c->model == PRSGD_MLP) {
+    const int L = lo.n_layers;
+    cv->yb = take(n * b * 4);
+    cv->xb = take(n * b * lo.ld[0] * es);
+    for (int l = 1; l < L; ++l) {
+      cv->h[l] = take(n * b * lo.ld[l] * es);
+      cv->delta[l] = take(n * b * lo.ld[l] * es);
+    }
+    cv->delta[L] = take(n * b * lo.ld[L] * es);
+    cv->logits = take(n * b * lo.ld[L] * 4);
+    if (bf16) cv->shadow = take(n * (size_t)lo.m_pad * 2);
+    if (!c->fused_update) cv->grads = take(n * (size_t)lo.m_pad * 4);
+  }
+  cv->total = off;
+}
+
+struct EventPair { hipEvent_t a, b; int kind; };
+
+}  // namespace
+
+struct prsgd_ctx {
+  prsgd_config cfg;
+  Layout lo;
+  Carve cv;
+  bool bf16;
+  hipStream_t stream;
+  const float* features;
+  const void* targets;
+  float* params;
+  char* ws;
+  int64_t t;
+  float lr;
+  char err[256];
+  // profiling
+  bool profiling;
+  std::vector<EventPair> pool;
+  size_t pool_used;
+  double prof_ms[KK_COUNT];
+  int64_t prof_n[KK_COUNT];
+  // scratch host buffer for padded <-> dense parameter conversion
+  std::vector<float> host_pad;
+
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  uint16_t* shadow() const { return bf16 ? at<uint16_t>(cv.shadow) : nullptr; }
+  float* grads() const { return cfg.fused_update ? nullptr : at<float>(cv.grads); }
+};
+
+namespace {
+
+int set_err(prsgd_ctx* ctx, int code, const char* fmt, const char* detail = "") {
+  if (ctx != nullptr) snprintf(ctx->err, sizeof(ctx->err), fmt, detail);
+  else snprintf(g_init_error, sizeof(g_init_error), fmt, detail);
+  return code;
+}
+int hip_fail(prsgd_ctx* ctx, hipError_t e, const char* what) {
+  char buf[200];
+  snprintf(buf, sizeof(buf), "%s: %s", what, hipGetErrorString(e));
+  return set_err(ctx, PRSGD_EHIP, "%s", buf);
+}
+
+// Drains finished event pairs into the per-kind totals.
+int profile_flush(prsgd_ctx* ctx) {
+  if (ctx->pool_used == 0) return PRSGD_OK;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "hipStreamSynchronize");
+  for (size_t i = 0; i < ctx->pool_used; ++i) {
+    float ms = 0.0f;
+    e = hipEventElapsedTime(&ms, ctx->pool[i].a, ctx->pool[i].b);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipEventElapsedTime");
+    ctx->prof_ms[ctx->pool[i].kind] += ms;
+    ctx->prof_n[ctx->pool[i].kind] += 1;
+  }
+  ctx->pool_used = 0;
+  return PRSGD_OK;
+}
+
+// Brackets one kernel launch with an event pair while profiling is on.
+struct Timed {
+  prsgd_ctx* ctx;
+  EventPair* ep = nullptr;
+  Timed(prsgd_ctx* c, int kind) : ctx(c) {
+    if (!c->profiling) return;
+    if (c->pool_used == c->pool.size() && profile_flush(c) != PRSGD_OK) return;
+    ep = &c->pool[c->pool_used++];
+    ep->kind = kind;
+    (void)hipEventRecord(ep->a, c->stream);
+  }
+  ~Timed() {
+    if (ep != nullptr) (void)hipEventRecord(ep->b, ctx->stream);
+  }
+};
+
+#define LAUNCH(ctx, kind, call)                                        \
+  do {                                                                 \
+    hipError_t e_;                                                     \
+    {                                                                  \
+      Timed timed_(ctx, kind);                                         \
+      e_ = (call);                                                     \
+    }                                                                  \
+    if (e_ != hipSuccess) return hip_fail(ctx, e_, kernel_kind_name(kind)); \
+  } while (0)
+
+// One local iteration of every (active) MLP worker: gradient observation + eq. (3).
+int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
+  const prsgd_config& c = ctx->cfg;
+  const Layout& lo = ctx->lo;
+  const Carve& cv = ctx->cv;
+  const int N = c.n_workers, B = c.batch, L = lo.n_layers;
+  const bool bf16 = ctx->bf16;
+  hipStream_t s = ctx->stream;
+
+  LAUNCH(ctx, KK_GATHER,
+         launch_gather(ctx->features, reinterpret_cast<const int32_t*>(ctx->targets),
+                       ctx->at<void>(cv.xb), ctx->at<int32_t>(cv.yb), ctx->at<int32_t>(cv.idx), N, B,
+                       lo.d[0], lo.ld[0], (long)c.rows_per_worker, c.seed, t, bf16, worker_steps, step,
+                       s));
+
+  GemmArgs base;
+  memset(&base, 0, sizeof(base));
+  base.act = c.activation;
+  base.lr = ctx->lr;
+  base.params = ctx->params;
+  base.grads = ctx->grads();
+  base.shadow = ctx->shadow();
+  base.p_gs = lo.m_pad;
+  base.worker_steps = worker_steps;
+  base.step = step;
+
+  auto act_in = [&](int l) -> const void* {   // H_l as stored (l = 0: the gathered batch)
+    return l == 0 ? ctx->at<void>(cv.xb) : ctx->at<void>(cv.h[l]);
+  };
+  // The matrix products read weights from the bf16 shadow (bf16 mode) or the fp32 master.
+  const void* wsrc = bf16 ? (const void*)ctx->shadow() : (const void*)ctx->params;
+
+  // forward
+  for (int l = 1; l <= L; ++l) {
+    GemmArgs p = base;
+    p.a = act_in(l - 1); p.a_gs = (long)B * lo.ld[l - 1]; p.lda = lo.ld[l - 1];
+    p.b = bf16 ? (const void*)(reinterpret_cast<const uint16_t*>(wsrc) + lo.w_off[l - 1])
+               : (const void*)(reinterpret_cast<const float*>(wsrc) + lo.w_off[l - 1]);
+    p.b_gs = lo.m_pad; p.ldb = lo.ld[l];
+    p.M = B; p.N = lo.d[l]; p.Kc = lo.d[l - 1];
+    p.b_off = lo.b_off[l - 1];
+    p.out_gs = (long)B * lo.ld[l]; p.ldo = lo.ld[l]; p.out_cols = lo.ld[l];
+    if (l < L) { p.epi = EPI_FWD_HIDDEN; p.out = ctx->at<void>(cv.h[l]); }
+    else { p.epi = EPI_FWD_LOGITS; p.out = ctx->at<void>(cv.logits); }
+    LAUNCH(ctx, KK_FWD, launch_gemm_fwd(p, N, bf16, s));
+  }
+
+  LAUNCH(ctx, KK_LOSS,
+         launch_softmax_xent(ctx->at<float>(cv.logits), ctx->at<int32_t>(cv.yb),
+                             ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.losses), N, B, lo.d[L],
+                             lo.ld[L], bf16, worker_steps, step, s));
+
+  // backward: D_{l-1} needs the pre-update W_l, so it runs before layer l's weight kernel
+  for (int l = L; l >= 1; --l) {
+    if (l > 1) {
+      GemmArgs p = base;
+      p.a = ctx->at<void>(cv.delta[l]); p.a_gs = (long)B * lo.ld[l]; p.lda = lo.ld[l];
+      p.b = bf16 ? (const void*)(reinterpret_cast<const uint16_t*>(wsrc) + lo.w_off[l - 1])
+                 : (const void*)(reinterpret_cast<const float*>(wsrc) + lo.w_off[l - 1]);
+      p.b_gs = lo.m_pad; p.ldb = lo.ld[l];
+      p.M = B; p.N = lo.d[l - 1]; p.Kc = lo.d[l];
+      p.epi = EPI_DX;
+      p.out = ctx->at<void>(cv.delta[l - 1]); p.out_gs = (long)B * lo.ld[l - 1];
+      p.ldo = lo.ld[l - 1]; p.out_cols = lo.ld[l - 1];
+      p.aux = act_in(l - 1); p.aux_gs = (long)B * lo.ld[l - 1]; p.ldaux = lo.ld[l - 1];
+      LAUNCH(ctx, KK_DX, launch_gemm_dx(p, N, bf16, s));
+    }
+    GemmArgs p = base;
+    p.a = act_in(l - 1); p.a_gs = (long)B * lo.ld[l - 1]; p.lda = lo.ld[l - 1];
+    p.b = ctx->at<void>(cv.delta[l]); p.b_gs = (long)B * lo.ld[l]; p.ldb = lo.ld[l];
+    p.M = lo.d[l - 1]; p.N = lo.d[l]; p.Kc = B;
+    p.epi = c.fused_update ? EPI_DW_FUSED : EPI_DW_GRAD;
+    p.w_off = lo.w_off[l - 1]; p.b_off = lo.b_off[l - 1]; p.ldw = lo.ld[l];
+    LAUNCH(ctx, KK_DW, launch_gemm_dw(p, N, bf16, s));
+  }
+
+  if (!c.fused_update) {
+    if (worker_steps == nullptr)
+      LAUNCH(ctx, KK_UPDATE, launch_update(ctx->params, ctx->grads(), ctx->shadow(),
+                                           (size_t)N * lo.m_pad, ctx->lr, s));
+    else
+      LAUNCH(ctx, KK_UPDATE, launch_update_masked(ctx->params, ctx->grads(), ctx->shadow(), lo.m_pad,
+                                                  N, ctx->lr, worker_steps, step, s));
+  }
+  return PRSGD_OK;
+}
+
+int pad_from_dense(const prsgd_ctx* ctx, const float* dense, float* padded) {
+  const Layout& lo = ctx->lo;
+  memset(padded, 0, sizeof(float) * (size_t)lo.m_pad);
+  if (lo.n_layers == 0) { memcpy(padded, dense, sizeof(float) * (size_t)lo.m); return 0; }
+  size_t src = 0;
+  for (int l = 1; l <= lo.n_layers; ++l) {
+    for (int r = 0; r < lo.d[l - 1]; ++r) {
+      memcpy(padded + lo.w_off[l - 1] + (size_t)r * lo.ld[l], dense + src, sizeof(float) * lo.d[l]);
+      src += lo.d[l];
+    }
+    memcpy(padded + lo.b_off[l - 1], dense + src, sizeof(float) * lo.d[l]);
+    src += lo.d[l];
+  }
+  return 0;
+}
+void dense_from_pad(const prsgd_ctx* ctx, const float* padded, float* dense) {
+  const Layout& lo = ctx->lo;
+  if (lo.n_layers == 0) { memcpy(dense, padded, sizeof(float) * (size_t)lo.m); return; }
+  size_t dst = 0;
+  for (int l = 1; l <= lo.n_layers; ++l) {
+    for (int r = 0; r < lo.d[l - 1]; ++r) {
+      memcpy(dense + dst, padded + lo.w_off[l - 1] + (size_t)r * lo.ld[l], sizeof(float) * lo.d[l]);
+      dst += lo.d[l];
+    }
+    memcpy(dense + dst, padded + lo.b_off[l - 1], sizeof(float) * lo.d[l]);
+    dst += lo.d[l];
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t prsgd_param_count(const prsgd_config* cfg) {
+  Layout lo;
+  char err[128];
+  return build_layout(cfg, &lo, err, sizeof(err)) ? (size_t)lo.m : 0;
+}
+size_t prsgd_param_stride(const prsgd_config* cfg) {
+  Layout lo;
+  char err[128];
+  return build_layout(cfg, &lo, err, sizeof(err)) ? (size_t)lo.m_pad : 0;
+}
+size_t prsgd_workspace_bytes(const prsgd_config* cfg) {
+  Layout lo;
+  char err[128];
+  if (!build_layout(cfg, &lo, err, sizeof(err))) return 0;
+  Carve cv;
+  build_carve(cfg, lo, &cv);
+  return cv.total;
+}
+
+int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* features_dev,
+               const void* targets_dev, void* params_dev, void* workspace_dev, void* hip_stream,
+               prsgd_ctx** out_ctx) {
+  if (out_ctx == nullptr) return set_err(nullptr, PRSGD_EINVAL, "out_ctx is null");
+  *out_ctx = nullptr;
+  Layout lo;
+  char err[128];
+  if (!build_layout(cfg, &lo, err, sizeof(err))) return set_err(nullptr, PRSGD_EINVAL, "%s", err);
+  if (x0_host == nullptr || features_dev == nullptr || targets_dev == nullptr || params_dev == nullptr ||
+      workspace_dev == nullptr)
+    return set_err(nullptr, PRSGD_EINVAL, "null buffer");
+  if (((uintptr_t)params_dev % kAlign) != 0 || ((uintptr_t)workspace_dev % kAlign) != 0)
+    return set_err(nullptr, PRSGD_EINVAL, "params_dev and workspace_dev must be 256-byte aligned");
+  if (((uintptr_t)features_dev % 16) != 0 || ((uintptr_t)targets_dev % 4) != 0)
+    return set_err(nullptr, PRSGD_EINVAL, "features_dev must be 16-byte and targets_dev 4-byte aligned");
+
+  prsgd_ctx* ctx = new (std::nothrow) prsgd_ctx();
+  if (ctx == nullptr) return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
+  ctx->cfg = *cfg;
+  ctx->lo = lo;
+  build_carve(cfg, lo, &ctx->cv);
+  ctx->bf16 = cfg->model == PRSGD_MLP && cfg->gemm_dtype == PRSGD_BF16;
+  ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  ctx->features = reinterpret_cast<const float*>(features_dev);
+  ctx->targets = targets_dev;
+  ctx->params = reinterpret_cast<float*>(params_dev);
+  ctx->ws = reinterpret_cast<char*>(workspace_dev);
+  ctx->t = 0;
+  ctx->lr = cfg->lr;
+  ctx->err[0] = 0;
+  ctx->profiling = false;
+  ctx->pool_used = 0;
+  memset(ctx->prof_ms, 0, sizeof(ctx->prof_ms));
+  memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
+  try {
+    ctx->host_pad.resize((size_t)lo.m_pad);
+  } catch (...) {
+    delete ctx;
+    return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
+  }
+
+  // Zero the workspace once: padding columns of every activation buffer must read as zero.
+  hipError_t e = hipMemsetAsync(ctx->ws, 0, ctx->cv.total, ctx->stream);
+  if (e == hipSuccess) {
+    pad_from_dense(ctx, x0_host, ctx->host_pad.data());
+    e = hipMemcpyAsync(ctx->at<float>(ctx->cv.mean), ctx->host_pad.data(), sizeof(float) * (size_t)lo.m_pad,
+                       hipMemcpyHostToDevice, ctx->stream);
+  }
+  if (e == hipSuccess)
+    e = launch_broadcast(ctx->at<float>(ctx->cv.mean), ctx->params, ctx->shadow(), lo.m_pad,
+                         cfg->n_workers, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) {
+    hip_fail(nullptr, e, "prsgd_init");
+    delete ctx;
+    return PRSGD_EHIP;
+  }
+  *out_ctx = ctx;
+  return PRSGD_OK;
+}
+
+int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (k < 0) return set_err(ctx, PRSGD_EINVAL, "k must be >= 0");
+  const prsgd_config& c = ctx->cfg;
+  if (c.model == PRSGD_LSQ) {
+    LAUNCH(ctx, KK_LSQ,
+           launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->params,
+                            ctx->at<float>(ctx->cv.losses), ctx->at<int32_t>(ctx->cv.idx), c.n_workers,
+                            ctx->lo.d[0], ctx->lo.m_pad, (long)c.rows_per_worker, c.batch, ctx->lr, c.seed,
+                            ctx->t, k, nullptr, ctx->stream));
+    ctx->t += k;
+    return PRSGD_OK;
+  }
+  for (int32_t s = 0; s < k; ++s) {
+    const int rc = mlp_step(ctx, ctx->t + 1, nullptr, 0);
+    if (rc != PRSGD_OK) return rc;
+    ctx->t += 1;
+  }
+  return PRSGD_OK;
+}
+
+int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (steps_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "steps_host is null");
+  const prsgd_config& c = ctx->cfg;
+  int32_t k_max = 0;
+  for (int i = 0; i < c.n_workers; ++i) {
+    if (steps_host[i] < 0) return set_err(ctx, PRSGD_EINVAL, "worker step counts must be >= 0");
+    if (steps_host[i] > k_max) k_max = steps_host[i];
+  }
+  int* steps_dev = ctx->at<int>(ctx->cv.steps);
+  // The pageable source may be reused by the caller right after return: wait for the copy.
+  hipError_t e = hipMemcpyAsync(steps_dev, steps_host, sizeof(int32_t) * c.n_workers,
+                                hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "copy of worker step counts");
+  if (c.model == PRSGD_LSQ) {
+    LAUNCH(ctx, KK_LSQ,
+           launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->params,
+                            ctx->at<float>(ctx->cv.losses), ctx->at<int32_t>(ctx->cv.idx), c.n_workers,
+                            ctx->lo.d[0], ctx->lo.m_pad, (long)c.rows_per_worker, c.batch, ctx->lr, c.seed,
+                            ctx->t, k_max, steps_dev, ctx->stream));
+    ctx->t += k_max;
+    return PRSGD_OK;
+  }
+  for (int32_t s = 0; s < k_max; ++s) {
+    const int rc = mlp_step(ctx, ctx->t + 1, steps_dev, s);
+    if (rc != PRSGD_OK) return rc;
+    ctx->t += 1;
+  }
+  return PRSGD_OK;
+}
+
+int prsgd_average(prsgd_ctx* ctx) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  LAUNCH(ctx, KK_AVERAGE,
+         launch_average(ctx->params, ctx->shadow(), ctx->lo.m_pad, ctx->cfg.n_workers, ctx->stream));
+  return PRSGD_OK;
+}
+
+int prsgd_run(prsgd_ctx* ctx, int64_t iterations, int32_t interval) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (iterations < 0 || interval < 1) return set_err(ctx, PRSGD_EINVAL, "iterations >= 0, interval >= 1");
+  int64_t left = iterations;
+  while (left > 0) {
+    int64_t k = interval - (ctx->t % interval);      // steps until the next multiple of I
+    if (k > left) k = left;
+    int rc = prsgd_local_steps(ctx, (int32_t)k);
+    if (rc != PRSGD_OK) return rc;
+    left -= k;
+    if (ctx->t % interval == 0) {
+      rc = prsgd_average(ctx);
+      if (rc != PRSGD_OK) return rc;
+    }
+  }
+  return PRSGD_OK;
+}
+
+int prsgd_read_params(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
+  if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
+  if (worker < -1 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
+  const float* src;
+  if (worker < 0) {
+    LAUNCH(ctx, KK_MEAN, launch_mean(ctx->params, ctx->at<float>(ctx->cv.mean), ctx->lo.m_pad,
+                                     ctx->cfg.n_workers, ctx->stream));
+    src = ctx->at<float>(ctx->cv.mean);
+  } else {
+    src = ctx->params + (size_t)worker * ctx->lo.m_pad;
+  }
+  hipError_t e = hipMemcpyAsync(ctx->host_pad.data(), src, sizeof(float) * (size_t)ctx->lo.m_pad,
+                                hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_params");
+  dense_from_pad(ctx, ctx->host_pad.data(), out_host);
+  return PRSGD_OK;
+}
+
+int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, size_t m) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (in_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "in_host is null");
+  if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
+  if (worker < -1 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
+  pad_from_dense(ctx, in_host, ctx->host_pad.data());
+  const size_t bytes = sizeof(float) * (size_t)ctx->lo.m_pad;
+  hipError_t e;
+  if (worker < 0) {
+    e = hipMemcpyAsync(ctx->at<float>(ctx->cv.mean), ctx->host_pad.data(), bytes, hipMemcpyHostToDevice,
+                       ctx->stream);
+    if (e == hipSuccess)
+      e = launch_broadcast(ctx->at<float>(ctx->cv.mean), ctx->params, ctx->shadow(), ctx->lo.m_pad,
+                           ctx->cfg.n_workers, ctx->stream);
+  } else {
+    float* dst = ctx->params + (size_t)worker * ctx->lo.m_pad;
+    e = hipMemcpyAsync(dst, ctx->host_pad.data(), bytes, hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess && ctx->bf16)
+      e = launch_refresh_shadow(dst, ctx->shadow() + (size_t)worker * ctx->lo.m_pad, ctx->lo.m_pad,
+                                ctx->stream);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_write_params");
+  return PRSGD_OK;
+}
+
+int prsgd_read_loss(prsgd_ctx* ctx, float* out_host) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
+  hipError_t e = hipMemcpyAsync(out_host, ctx->at<float>(ctx->cv.losses), sizeof(float) * ctx->cfg.n_workers,
+                                hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_loss");
+  return PRSGD_OK;
+}
+
+int prsgd_read_indices(prsgd_ctx* ctx, int32_t* out_host) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
+  const size_t bytes = sizeof(int32_t) * (size_t)ctx->cfg.n_workers * ctx->cfg.batch;
+  hipError_t e = hipMemcpyAsync(out_host, ctx->at<int32_t>(ctx->cv.idx), bytes, hipMemcpyDeviceToHost,
+                                ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_indices");
+  return PRSGD_OK;
+}
+
+int prsgd_sample_indices(uint64_t seed, int32_t n_workers, int32_t batch, int64_t rows_per_worker,
+                         int64_t t_first, int32_t n_steps, int32_t* out_dev, void* hip_stream) {
+  if (out_dev == nullptr || n_workers < 1 || batch < 1 || n_steps < 0 || t_first < 0 ||
+      rows_per_worker < 1 || rows_per_worker > (1LL << 31) ||
+      (rows_per_worker & (rows_per_worker - 1)) != 0)
+    return set_err(nullptr, PRSGD_EINVAL, "prsgd_sample_indices: bad argument");
+  hipError_t e = launch_sample_indices(seed, n_workers, batch, (long)rows_per_worker, t_first, n_steps,
+                                       out_dev, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(nullptr, e, "prsgd_sample_indices");
+  return PRSGD_OK;
+}
+
+int prsgd_sgd_update(float* x_dev, const float* g_dev, uint16_t* shadow_dev, size_t count, float lr,
+                     void* hip_stream) {
+  if (x_dev == nullptr || g_dev == nullptr) return set_err(nullptr, PRSGD_EINVAL, "null buffer");
+  if (((uintptr_t)x_dev % 16) != 0 || ((uintptr_t)g_dev % 16) != 0 || ((uintptr_t)shadow_dev % 8) != 0)
+    return set_err(nullptr, PRSGD_EINVAL, "prsgd_sgd_update: misaligned buffer");
+  hipError_t e = launch_update(x_dev, g_dev, shadow_dev, count, lr, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(nullptr, e, "prsgd_sgd_update");
+  return PRSGD_OK;
+}
+
+int prsgd_set_lr(prsgd_ctx* ctx, float lr) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (!(lr == lr)) return set_err(ctx, PRSGD_EINVAL, "lr is NaN");
+  ctx->lr = lr;
+  return PRSGD_OK;
+}
+int prsgd_set_iteration(prsgd_ctx* ctx, int64_t t) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (t < 0) return set_err(ctx, PRSGD_EINVAL, "t must be >= 0");
+  ctx->t = t;
+  return PRSGD_OK;
+}
+int64_t prsgd_iteration(const prsgd_ctx* ctx) { return ctx == nullptr ? -1 : ctx->t; }
+
+int prsgd_profile_enable(prsgd_ctx* ctx, int32_t on) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (on && ctx->pool.empty()) {
+    constexpr size_t kPairs = 2048;
+    try {
+      ctx->pool.reserve(kPairs);
+    } catch (...) {
+      return set_err(ctx, PRSGD_ENOMEM, "out of host memory");
+    }
+    for (size_t i = 0; i < kPairs; ++i) {
+      EventPair ep;
+      hipError_t e = hipEventCreate(&ep.a);
+      if (e == hipSuccess) {
+        e = hipEventCreate(&ep.b);
+        if (e != hipSuccess) (void)hipEventDestroy(ep.a);
+      }
+      if (e != hipSuccess) return hip_fail(ctx, e, "hipEventCreate");
+      ep.kind = 0;
+      ctx->pool.push_back(ep);
+    }
+  }
+  if (!on) {
+    const int rc = profile_flush(ctx);
+    if (rc != PRSGD_OK) return rc;
+  }
+  ctx->profiling = on != 0;
+  return PRSGD_OK;
+}
+
+int prsgd_profile_read(prsgd_ctx* ctx, prsgd_kernel_stat* out, int32_t max) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (out == nullptr || max < 0) return set_err(ctx, PRSGD_EINVAL, "bad output buffer");
+  const int rc = profile_flush(ctx);
+  if (rc != PRSGD_OK) return rc;
+  int n = 0;
+  for (int k = 0; k < KK_COUNT; ++k) {
+    if (ctx->prof_n[k] == 0) continue;
+    if (n < max) {
+      memset(&out[n], 0, sizeof(out[n]));
+      snprintf(out[n].name, sizeof(out[n].name), "%s", kernel_kind_name(k));
+      out[n].launches = ctx->prof_n[k];
+      out[n].total_ms = ctx->prof_ms[k];
+    }
+    ++n;
+  }
+  memset(ctx->prof_ms, 0, sizeof(ctx->prof_ms));
+  memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
+  return n;
+}
+
+int prsgd_destroy(prsgd_ctx* ctx) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  for (auto& ep : ctx->pool) {
+    (void)hipEventDestroy(ep.a);
+    (void)hipEventDestroy(ep.b);
+  }
+  delete ctx;
+  return e == hipSuccess ? PRSGD_OK : PRSGD_EHIP;
+}
+
+const char* prsgd_last_error(const prsgd_ctx* ctx) { return ctx != nullptr ? ctx->err : g_init_error; }
+
+}  // extern "C"

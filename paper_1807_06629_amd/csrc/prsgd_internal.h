@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of libprsgd (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prsgd.h"
+
+namespace prsgd {
+
+constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes per workgroup
+constexpr int kWave = 64;
+constexpr int kMaxBatch = 4096;
+constexpr int kMaxLsqDim = 8192;
+
+// Device layout of one replica x_i (floats).  An MLP replica is
+//   [W_1][b_1][W_2][b_2]...   W_l stored row-major as [d_{l-1}][ld_l], ld_l = d_l rounded up
+// to a multiple of 8 so that every row starts 32-byte aligned; each segment starts on a
+// 64-float boundary.  All padding holds zeros and stays zero under update and average.
+struct Layout {
+  int  n_layers;                     // L (0 for least squares)
+  int  d[PRSGD_MAX_DIMS];            // logical widths d_0..d_L
+  int  ld[PRSGD_MAX_DIMS];           // padded widths
+  long w_off[PRSGD_MAX_DIMS];        // offset of W_l, index l-1
+  long b_off[PRSGD_MAX_DIMS];        // offset of b_l, index l-1
+  long m;                            // logical parameter count
+  long m_pad;                        // replica stride in floats
+};
+
+enum GemmEpilogue {
+  EPI_FWD_HIDDEN = 0,   // out = T(phi(acc + bias))
+  EPI_FWD_LOGITS = 1,   // out = float(acc + bias)
+  EPI_DX = 2,           // out = T(acc * phi'(aux))
+  EPI_DW_FUSED = 3,     // W <- W - lr * acc (and bf16 shadow), b likewise from column sums
+  EPI_DW_GRAD = 4,      // G_W = acc, G_b = column sums
+};
+
+// One grouped matrix product: for every group (replica) g
+//   C_g[m][n] = sum_c A_g(m, c) * B_g(n, c),   m < M, n < N, c < Kc
+// followed by an epilogue.  Operand element (r, c) sits at base + g*gs + r*ld + c when the
+// operand is contraction-contiguous, or at base + g*gs + c*ld + r when it is transposed.
+struct GemmArgs {
+  const void* a; long a_gs; int lda;
+  const void* b; long b_gs; int ldb;
+  int M, N, Kc;
+  int epi;
+  int act;                            // PRSGD_TANH | PRSGD_RELU
+  float lr;
+  // parameters / gradients (fp32, replica stride m_pad), bf16 shadow of the parameters
+  float* params; float* grads; uint16_t* shadow; long p_gs;
+  long w_off, b_off; int ldw;
+  // activation-like output (element type T, or float for logits) and auxiliary input
+  void* out; long out_gs; int ldo; int out_cols;
+  const void* aux; long aux_gs; int ldaux;
+  // Algorithm 3: group g is skipped once step >= worker_steps[g] (nullptr = all active)
+  const int* worker_steps; int step;
+};
+
+enum KernelKind {
+  KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
+  KK_LSQ, KK_COUNT
+};
+const char* kernel_kind_name(int kind);
+
+// ---- launchers (each returns the hipError_t of the launch) --------------------------------
+hipError_t launch_gemm_fwd(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
+hipError_t launch_gemm_dx(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
+hipError_t launch_gemm_dw(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
+
+hipError_t launch_gather(const float* features, const int32_t* labels, void* xb, int32_t* yb,
+                         int32_t* idx, int n_workers, int batch, int d0, int ld0, long rows,
+                         uint64_t seed, int64_t t, bool bf16, const int* worker_steps, int step,
+                         hipStream_t s);
+hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long rows, int64_t t_first,
+                                 int n_steps, int32_t* out, hipStream_t s);
+hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* losses,
+                               int n_workers, int batch, int n_classes, int ldc, bool bf16,
+                               const int* worker_steps, int step, hipStream_t s);
+
+hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, hipStream_t s);
+hipError_t launch_mean(const float* params, float* out, long m_pad, int n_workers, hipStream_t s);
+hipError_t launch_broadcast(const float* src, float* params, uint16_t* shadow, long m_pad,
+                            int n_workers, hipStream_t s);
+hipError_t launch_refresh_shadow(const float* params, uint16_t* shadow, long count, hipStream_t s);
+hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t count, float lr,
+                         hipStream_t s);
+hipError_t launch_update_masked(float* x, const float* g, uint16_t* shadow, long m_pad, int n_workers,
+                                float lr, const int* worker_steps, int step, hipStream_t s);
+
+hipError_t launch_lsq_steps(const float* features, const float* targets, float* params, float* losses,
+                            int32_t* idx, int n_workers, int d, long m_pad, long rows, int batch,
+                            float lr, uint64_t seed, int64_t t0, int k, const int* worker_steps,
+                            hipStream_t s);
+
+// ---- small device helpers ------------------------------------------------------------------
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);          // round to nearest, ties to even
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies
+// with the key advanced by the Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) { k0 += W0; k1 += W1; }
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Row drawn by worker `worker` at iteration t for minibatch slot j (top log2(n) bits).
+__device__ __forceinline__ int32_t sample_row(uint64_t seed, uint32_t worker, uint64_t t, uint32_t j,
+                                              int log2n) {
+  uint32_t w[4];
+  philox4x32_10(j >> 2, (uint32_t)t, (uint32_t)(t >> 32), worker, (uint32_t)seed,
+                (uint32_t)(seed >> 32), w);
+  const uint32_t sel = j & 3u;
+  const uint32_t word = sel == 0 ? w[0] : sel == 1 ? w[1] : sel == 2 ? w[2] : w[3];
+  return log2n == 0 ? 0 : (int32_t)(word >> (32 - log2n));
+}
+
+}  // namespace prsgd
