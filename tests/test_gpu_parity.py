@@ -353,5 +353,3 @@ def test_argument_errors_leave_the_context_usable(P, D):
     assert P.prsgd_iteration(h) == 0
     assert np.array_equal(P.prsgd_read_params(h, 0), inp["x0"])
     P.prsgd_destroy(h)
-EOF
-echo ok
