@@ -183,9 +183,16 @@ def test_c3_shape_noniid_reduced(P, D):
     w = get_workload("c3").scaled(n_workers=4, rows_per_worker=512, iterations=6, interval=3)
     inp = make_inputs(w)
     h = _open(D, w, inp)
-    P.prsgd_run(h, w.iterations, w.interval)
-    want = oracle_run(w, inp)
-    assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=BF16_LOSS_TOL)
+    log = []
+    want = oracle_run(w, inp, record=log.append)
+    # loss of every iteration; once the (nearly separable) minibatch loss has fallen below
+    # ~1e-2 a single bf16 rounding flip of one activation moves it by more than 2 %, so the
+    # relative gate carries an absolute floor of 2e-2 * 0.02
+    for rec in log:
+        P.prsgd_run(h, 1, w.interval)
+        got = P.prsgd_read_loss(h)
+        assert np.allclose(got, rec["losses"], rtol=BF16_LOSS_TOL, atol=BF16_LOSS_TOL * 0.02), \
+            (rec["t"], got, rec["losses"])
     assert rel_err(D.read_all(h), want["x"]) <= 5e-3
     P.prsgd_destroy(h)
 
