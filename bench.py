@@ -100,6 +100,9 @@ def main() -> int:
     ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows", type=int, default=None, help="rows per worker (default: workload's)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="time the plain copy kernel (known traffic) instead of a workload")
+    ap.add_argument("--copy-mib", type=int, default=1024)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the N workers are simulated on it); "
@@ -113,6 +116,26 @@ def main() -> int:
         build()
     from paper_1807_06629_amd import drivers, prsgd
     from workloads import get_workload, make_inputs
+
+    if args.calibrate_copy:
+        n_bytes = args.copy_mib << 20
+        src = torch.ones(n_bytes // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        reps = args.steps if args.steps is not None else 20
+        for _ in range(3):
+            prsgd.prsgd_copy_bytes(dst, src)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(reps):
+            prsgd.prsgd_copy_bytes(dst, src)
+        stop.record()
+        torch.cuda.synchronize()
+        ms = start.elapsed_time(stop) / reps
+        print(json.dumps({"kernel": "copy_kernel", "bytes_read": n_bytes, "bytes_written": n_bytes,
+                          "launches": reps + 3, "avg_us": 1e3 * ms,
+                          "GBps": 2 * n_bytes / (ms * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": 2 * n_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}))
+        return 0
 
     w = get_workload(args.workload)
     if args.interval is not None:

@@ -147,6 +147,14 @@ int prsgd_sample_indices(uint64_t seed, int32_t n_workers, int32_t batch, int64_
 int prsgd_sgd_update(float* x_dev, const float* g_dev, uint16_t* shadow_dev, size_t count,
                      float lr, void* hip_stream);
 
+/*
+ * Measurement aid, not part of the method: a plain device-to-device copy kernel of `bytes`
+ * bytes (a multiple of 16; both pointers 16-byte aligned) whose traffic is known exactly.
+ * Used to calibrate achievable HBM bandwidth and the fetch/write hardware counters against
+ * which the kernels above are compared.
+ */
+int prsgd_copy_bytes(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
+
 int     prsgd_set_lr(prsgd_ctx* ctx, float lr);           /* gamma for later iterations      */
 int     prsgd_set_iteration(prsgd_ctx* ctx, int64_t t);   /* resume: counter of done iterations */
 int64_t prsgd_iteration(const prsgd_ctx* ctx);            /* iterations done so far, <0 on null */

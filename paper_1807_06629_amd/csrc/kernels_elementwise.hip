@@ -13,56 +13,80 @@ namespace prsgd {
 
 constexpr int kChunk = 8;   // replica loads kept in flight per thread
 
-__device__ __forceinline__ float4 add4(float4 a, float4 b) {
-  return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+// Streaming accesses: the replica buffer is far larger than any cache level and every element
+// is touched once per pass, so loads and stores carry the non-temporal hint.
+template <bool NT> __device__ __forceinline__ f32x4_t ld4(const f32x4_t* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
 }
+template <bool NT> __device__ __forceinline__ void st4(f32x4_t* p, f32x4_t v) {
+  if (NT) __builtin_nontemporal_store(v, p); else *p = v;
+}
+template <bool NT> __device__ __forceinline__ void st2(u32x2_t* p, u32x2_t v) {
+  if (NT) __builtin_nontemporal_store(v, p); else *p = v;
+}
+
 __device__ __forceinline__ uint2 pack_bf16x4(float4 v) {
   uint2 r;
   r.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
   r.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
   return r;
 }
+__device__ __forceinline__ u32x2_t pack_bf16x4(f32x4_t v) {
+  u32x2_t r;
+  r.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
+  r.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
+  return r;
+}
 
-// Sum of column `col` (float4 index) over the replicas, ascending i.
-__device__ __forceinline__ float4 replica_sum(const float4* __restrict__ p, size_t stride4, size_t col,
-                                              int n) {
-  float4 s = p[col];
+// Sum of column `col` (16-byte index) over the replicas, ascending i.
+template <bool NT>
+__device__ __forceinline__ f32x4_t replica_sum(const f32x4_t* __restrict__ p, size_t stride4, size_t col,
+                                               int n) {
+  f32x4_t s = ld4<NT>(p + col);
   int i = 1;
   for (; i + kChunk <= n; i += kChunk) {
-    float4 v[kChunk];
+    f32x4_t v[kChunk];
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) v[u] = p[(size_t)(i + u) * stride4 + col];
+    for (int u = 0; u < kChunk; ++u) v[u] = ld4<NT>(p + (size_t)(i + u) * stride4 + col);
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) s = add4(s, v[u]);
+    for (int u = 0; u < kChunk; ++u) s += v[u];
   }
-  for (; i < n; ++i) s = add4(s, p[(size_t)i * stride4 + col]);
+  if (i < n) {
+    f32x4_t v[kChunk];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u)
+      if (i + u < n) v[u] = ld4<NT>(p + (size_t)(i + u) * stride4 + col);
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u)
+      if (i + u < n) s += v[u];
+  }
   return s;
 }
 
-template <bool SHADOW>
-__global__ __launch_bounds__(kThreads) void average_kernel(float4* __restrict__ params,
-                                                           uint2* __restrict__ shadow, size_t stride4,
+template <bool SHADOW, bool NT>
+__global__ __launch_bounds__(kThreads) void average_kernel(f32x4_t* __restrict__ params,
+                                                           u32x2_t* __restrict__ shadow, size_t stride4,
                                                            int n, float n_f) {
   for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
        col += (size_t)gridDim.x * kThreads) {
-    const float4 s = replica_sum(params, stride4, col, n);
-    const float4 mean = make_float4(s.x / n_f, s.y / n_f, s.z / n_f, s.w / n_f);
-    for (int i = 0; i < n; ++i) params[(size_t)i * stride4 + col] = mean;
+    const f32x4_t mean = replica_sum<NT>(params, stride4, col, n) / n_f;
+    for (int i = 0; i < n; ++i) st4<NT>(params + (size_t)i * stride4 + col, mean);
     if (SHADOW) {
-      const uint2 h = pack_bf16x4(mean);
-      for (int i = 0; i < n; ++i) shadow[(size_t)i * stride4 + col] = h;
+      const u32x2_t h = pack_bf16x4(mean);
+      for (int i = 0; i < n; ++i) st2<NT>(shadow + (size_t)i * stride4 + col, h);
     }
   }
 }
 
-__global__ __launch_bounds__(kThreads) void mean_kernel(const float4* __restrict__ params,
-                                                        float4* __restrict__ out, size_t stride4, int n,
+__global__ __launch_bounds__(kThreads) void mean_kernel(const f32x4_t* __restrict__ params,
+                                                        f32x4_t* __restrict__ out, size_t stride4, int n,
                                                         float n_f) {
   for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
-       col += (size_t)gridDim.x * kThreads) {
-    const float4 s = replica_sum(params, stride4, col, n);
-    out[col] = make_float4(s.x / n_f, s.y / n_f, s.z / n_f, s.w / n_f);
-  }
+       col += (size_t)gridDim.x * kThreads)
+    out[col] = replica_sum<true>(params, stride4, col, n) / n_f;
 }
 
 __global__ __launch_bounds__(kThreads) void broadcast_kernel(const float4* __restrict__ src,
@@ -139,6 +163,14 @@ __global__ __launch_bounds__(kThreads) void update_masked_kernel(float4* __restr
   }
 }
 
+// Plain streaming copy with exactly known traffic (bandwidth / counter calibration).
+__global__ __launch_bounds__(kThreads) void copy_kernel(float4* __restrict__ dst,
+                                                        const float4* __restrict__ src, size_t count4) {
+  for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < count4;
+       k += (size_t)gridDim.x * kThreads)
+    dst[k] = src[k];
+}
+
 static int grid_for(size_t items, int max_blocks) {
   size_t b = (items + kThreads - 1) / kThreads;
   if (b < 1) b = 1;
@@ -149,24 +181,30 @@ static int grid_for(size_t items, int max_blocks) {
 // 256 CUs x 8 resident workgroups: enough waves to cover HBM latency without a long tail.
 constexpr int kStreamBlocks = 256 * 8;
 
-hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, hipStream_t s) {
+hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, bool streaming,
+                          hipStream_t s) {
   const size_t stride4 = (size_t)m_pad / 4;
-  const int grid = grid_for(stride4, kStreamBlocks);
-  if (shadow != nullptr)
-    hipLaunchKernelGGL(average_kernel<true>, dim3(grid), dim3(kThreads), 0, s,
-                       reinterpret_cast<float4*>(params), reinterpret_cast<uint2*>(shadow), stride4,
-                       n_workers, (float)n_workers);
-  else
-    hipLaunchKernelGGL(average_kernel<false>, dim3(grid), dim3(kThreads), 0, s,
-                       reinterpret_cast<float4*>(params), (uint2*)nullptr, stride4, n_workers,
-                       (float)n_workers);
+  // One column per thread in a single pass (measured best); the non-temporal variant is for
+  // replica sets far beyond the 256 MB last-level cache.
+  const bool nt = streaming;
+  const int grid = grid_for(stride4, 65536);
+  f32x4_t* p4 = reinterpret_cast<f32x4_t*>(params);
+  u32x2_t* s2 = reinterpret_cast<u32x2_t*>(shadow);
+  const float n_f = (float)n_workers;
+  if (shadow != nullptr) {
+    if (nt) hipLaunchKernelGGL((average_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
+    else hipLaunchKernelGGL((average_kernel<true, false>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
+  } else {
+    if (nt) hipLaunchKernelGGL((average_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
+    else hipLaunchKernelGGL((average_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_mean(const float* params, float* out, long m_pad, int n_workers, hipStream_t s) {
   const size_t stride4 = (size_t)m_pad / 4;
   hipLaunchKernelGGL(mean_kernel, dim3(grid_for(stride4, kStreamBlocks)), dim3(kThreads), 0, s,
-                     reinterpret_cast<const float4*>(params), reinterpret_cast<float4*>(out), stride4,
+                     reinterpret_cast<const f32x4_t*>(params), reinterpret_cast<f32x4_t*>(out), stride4,
                      n_workers, (float)n_workers);
   return hipGetLastError();
 }
@@ -185,6 +223,14 @@ hipError_t launch_refresh_shadow(const float* params, uint16_t* shadow, long cou
   hipLaunchKernelGGL(refresh_shadow_kernel, dim3(grid_for(count4, kStreamBlocks)), dim3(kThreads), 0,
                      s, reinterpret_cast<const float4*>(params), reinterpret_cast<uint2*>(shadow),
                      count4);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const size_t count4 = bytes / 16;
+  if (count4 == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_kernel, dim3(grid_for(count4, kStreamBlocks)), dim3(kThreads), 0, s,
+                     reinterpret_cast<float4*>(dst), reinterpret_cast<const float4*>(src), count4);
   return hipGetLastError();
 }
 

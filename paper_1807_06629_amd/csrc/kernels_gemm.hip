@@ -29,6 +29,7 @@ struct TF32 {
   static constexpr int KSTEP = 2;    // contraction depth of one MFMA
   static constexpr int BK = 32;      // contraction depth of one LDS tile
   static constexpr int PADC = 1;
+  static constexpr int PADT = 0;     // row padding of a transposed tile
   static constexpr bool kBf16 = false;
 };
 struct TBF16 {
@@ -38,6 +39,7 @@ struct TBF16 {
   static constexpr int KSTEP = 16;
   static constexpr int BK = 64;
   static constexpr int PADC = 8;
+  static constexpr int PADT = 16;    // 4 consecutive k rows of a transpose read hit distinct banks
   static constexpr bool kBf16 = true;
 };
 
@@ -50,84 +52,112 @@ template <> __device__ __forceinline__ float from_elem<TBF16>(uint16_t v) { retu
 
 // LDS footprint (elements) of a ROWS x BK operand tile.
 template <typename T, int ROWS, int KIND> struct TileShape {
-  static constexpr int kStride = (KIND == OP_CONTIG) ? (T::BK + T::PADC) : ROWS;
-  static constexpr int kElems = (KIND == OP_CONTIG) ? ROWS * kStride : T::BK * ROWS;
+  static constexpr int kStride = (KIND == OP_CONTIG) ? (T::BK + T::PADC) : (ROWS + T::PADT);
+  static constexpr int kElems = (KIND == OP_CONTIG) ? ROWS * kStride : T::BK * kStride;
 };
 
-// Copies a ROWS x BK operand tile from global memory into LDS (zero-filled outside the operand).
+// Moves a ROWS x BK operand tile from global memory to LDS in two halves so that the global
+// loads of tile k+1 can be in flight while tile k is multiplied: fetch() fills registers with
+// 16-byte vectors (zero outside the operand), stash() writes them to LDS.
 //   OP_CONTIG: element (r, c) at src[r * ld + c]; LDS [ROWS][BK + PADC]
-//   OP_TRANS : element (r, c) at src[c * ld + r]; LDS [BK][ROWS]
+//   OP_TRANS : element (r, c) at src[c * ld + r]; LDS [BK][ROWS + PADT]
 // Vector loads run along the memory-contiguous index; a vector that starts inside the logical
 // extent may run into the zero padding every buffer carries up to a multiple of 8 elements.
-template <typename T, int ROWS, int KIND>
-__device__ __forceinline__ void load_tile(typename T::elem* __restrict__ lds,
-                                          const typename T::elem* __restrict__ src, int ld,
-                                          int row0, int n_rows, int c0, int n_c, int tid) {
+template <typename T, int ROWS, int KIND> struct TileIO {
   using E = typename T::elem;
-  constexpr int V = T::V, BK = T::BK;
-  if (KIND == OP_CONTIG) {
-    constexpr int VPR = BK / V;
-    constexpr int TOTAL = ROWS * VPR;
-    constexpr int STRIDE = TileShape<T, ROWS, KIND>::kStride;
+  static constexpr int V = T::V, BK = T::BK;
+  static constexpr int VECS = ROWS * BK / V;
+  static constexpr int NPT = VECS / kThreads;            // vectors per thread
+  static_assert(VECS % kThreads == 0, "tile must split evenly over the workgroup");
+  static constexpr int STRIDE = TileShape<T, ROWS, KIND>::kStride;
+
+  // Returns the validity mask of the NPT vectors (bit q set = inside the operand).
+  __device__ static __forceinline__ uint32_t fetch(uint4 (&reg)[NPT], const E* __restrict__ src, int ld,
+                                                   int row0, int n_rows, int c0, int n_c, int tid) {
+    uint32_t mask = 0;
 #pragma unroll
-    for (int v0 = 0; v0 < TOTAL; v0 += kThreads) {
-      const int v = v0 + tid;
-      if (TOTAL % kThreads != 0 && v >= TOTAL) break;
-      const int r = v / VPR, cv = (v % VPR) * V;
-      const int row = row0 + r, c = c0 + cv;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (row < n_rows && c < n_c)
-        val = *reinterpret_cast<const uint4*>(src + (size_t)row * ld + c);
-      E* dst = lds + r * STRIDE + cv;
-      if (T::kBf16) {
-        *reinterpret_cast<uint4*>(dst) = val;
-      } else {                                   // odd row stride: four 4-byte stores
-        uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
-        d32[0] = val.x; d32[1] = val.y; d32[2] = val.z; d32[3] = val.w;
+    for (int q = 0; q < NPT; ++q) {
+      const int v = q * kThreads + tid;
+      // Branch-free: an out-of-range vector loads element (0, 0) instead and is zeroed when it
+      // is written to LDS, so nothing waits on the load here and the loads stay countable for
+      // the compiler's vmcnt bookkeeping across the pipeline.
+      bool ok;
+      size_t off;
+      if (KIND == OP_CONTIG) {
+        constexpr int VPR = BK / V;
+        const int row = row0 + v / VPR, c = c0 + (v % VPR) * V;
+        ok = row < n_rows && c < n_c;
+        off = (size_t)row * ld + c;
+      } else {
+        constexpr int VPC = ROWS / V;
+        const int cc = c0 + v / VPC, row = row0 + (v % VPC) * V;
+        ok = cc < n_c && row < n_rows;
+        off = (size_t)cc * ld + row;
+      }
+      reg[q] = *reinterpret_cast<const uint4*>(src + (ok ? off : (size_t)0));
+      mask |= (ok ? 1u : 0u) << q;
+    }
+    return mask;
+  }
+
+  __device__ static __forceinline__ void stash(E* __restrict__ lds, const uint4 (&reg_in)[NPT],
+                                               uint32_t mask, int tid) {
+#pragma unroll
+    for (int q = 0; q < NPT; ++q) {
+      const int v = q * kThreads + tid;
+      const uint32_t keep = 0u - ((mask >> q) & 1u);      // all ones inside the operand, else zero
+      uint4 reg[1];
+      reg[0] = make_uint4(reg_in[q].x & keep, reg_in[q].y & keep, reg_in[q].z & keep, reg_in[q].w & keep);
+      if (KIND == OP_CONTIG) {
+        constexpr int VPR = BK / V;
+        E* dst = lds + (v / VPR) * STRIDE + (v % VPR) * V;
+        if (T::kBf16) {
+          *reinterpret_cast<uint4*>(dst) = reg[0];
+        } else {                                   // odd row stride: four 4-byte stores
+          uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+          d32[0] = reg[0].x; d32[1] = reg[0].y; d32[2] = reg[0].z; d32[3] = reg[0].w;
+        }
+      } else {
+        constexpr int VPC = ROWS / V;
+        *reinterpret_cast<uint4*>(lds + (v / VPC) * STRIDE + (v % VPC) * V) = reg[0];
       }
     }
-  } else {
-    constexpr int VPC = ROWS / V;
-    constexpr int TOTAL = BK * VPC;
-#pragma unroll
-    for (int v0 = 0; v0 < TOTAL; v0 += kThreads) {
-      const int v = v0 + tid;
-      if (TOTAL % kThreads != 0 && v >= TOTAL) break;
-      const int c = v / VPC, rv = (v % VPC) * V;
-      const int row = row0 + rv, cc = c0 + c;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (cc < n_c && row < n_rows)
-        val = *reinterpret_cast<const uint4*>(src + (size_t)cc * ld + row);
-      *reinterpret_cast<uint4*>(lds + c * ROWS + rv) = val;
-    }
   }
-}
+};
 
 // MFMA operand fragment of lane (r = lane % 32, kb = lane / 32) for tile row `row` and the
 // kk-th KSTEP slice.  A and B fragments use the same (kb, e) -> contraction index map, which is
 // all the instruction needs for the product to be the plain sum over c.
-template <typename T, int ROWS, int KIND>
-__device__ __forceinline__ typename T::frag load_frag(const typename T::elem* __restrict__ lds,
-                                                      int row, int kk, int kb);
-
 template <int ROWS, int KIND>
 __device__ __forceinline__ float load_frag_f32(const float* __restrict__ lds, int row, int kk, int kb) {
   if (KIND == OP_CONTIG) return lds[row * TileShape<TF32, ROWS, KIND>::kStride + kk * 2 + kb];
-  return lds[(kk * 2 + kb) * ROWS + row];
+  return lds[(kk * 2 + kb) * TileShape<TF32, ROWS, KIND>::kStride + row];
 }
+// bf16 fragment.  A contraction-contiguous tile gives it in one 16-byte read.  A transposed
+// tile [c][row] is read with the LDS transpose load (ds_read_b64_tr_b16): inside each group of
+// 16 lanes, lane r supplies the address of a 4-element row M[r] and lane i receives
+// M[4j + i/4][i%4], j = 0..3.  Addressing lane r at (c = c0 + r/4, rows 4*(r%4)..+3) therefore
+// hands lane i the four consecutive c of row i: a 4(c) x 16(row) block transposed in flight.
+// Two such loads give the eight contraction elements of the fragment.
 template <int ROWS, int KIND>
-__device__ __forceinline__ bf16x8_t load_frag_bf16(const uint16_t* __restrict__ lds, int row, int kk,
-                                                   int kb) {
-  u16x8_t u;
+__device__ __forceinline__ bf16x8_t load_frag_bf16(const uint16_t* __restrict__ lds, int row_block,
+                                                   int kk, int lane) {
+  constexpr int STRIDE = TileShape<TBF16, ROWS, KIND>::kStride;
   if (KIND == OP_CONTIG) {
-    u = *reinterpret_cast<const u16x8_t*>(lds + row * TileShape<TBF16, ROWS, KIND>::kStride +
-                                          kk * 16 + kb * 8);
+    const u16x8_t u = *reinterpret_cast<const u16x8_t*>(lds + (row_block + (lane & 31)) * STRIDE +
+                                                        kk * 16 + (lane >> 5) * 8);
+    return __builtin_bit_cast(bf16x8_t, u);
   } else {
-    const uint16_t* p = lds + (kk * 16 + kb * 8) * ROWS + row;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) u[e] = p[e * ROWS];
+    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+    typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
+    const int g = lane >> 4, r = lane & 15;
+    const int c = kk * 16 + 8 * (g >> 1) + (r >> 2);
+    const int row = row_block + 16 * (g & 1) + 4 * (r & 3);
+    const uint16_t* p = lds + c * STRIDE + row;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + 4 * STRIDE));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
-  return __builtin_bit_cast(bf16x8_t, u);
 }
 
 __device__ __forceinline__ f32x16_t mfma(float a, float b, f32x16_t c) {
@@ -147,25 +177,68 @@ __device__ __forceinline__ float act_bwd_from_h(float h, int act) {
 template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   using E = typename T::elem;
+  using IOA = TileIO<T, BM, AKIND>;
+  using IOB = TileIO<T, BN, BKIND>;
   constexpr int BK = T::BK;
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
+  constexpr int A_ELEMS = TileShape<T, BM, AKIND>::kElems, B_ELEMS = TileShape<T, BN, BKIND>::kElems;
   static_assert(WM * WN == 4, "4 wavefronts per workgroup");
   static_assert(TM >= 1 && TN >= 1, "tile too small for the wavefront grid");
+  static_assert((A_ELEMS * sizeof(E)) % 16 == 0 && (B_ELEMS * sizeof(E)) % 16 == 0, "LDS alignment");
 
-  const int g = blockIdx.z;
+  // Workgroup -> (group, tile).  The hardware deals consecutive workgroups round-robin to the
+  // 8 XCDs; when the group count is a multiple of 8 all tiles of a group land on one XCD, so the
+  // group's activations and weight panel stay in that XCD's L2.
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int tiles = tiles_m * tiles_n;
+  int g, tile;
+  if ((p.n_groups & 7) == 0) {
+    const int slot = blockIdx.x >> 3;
+    g = (blockIdx.x & 7) + 8 * (slot / tiles);
+    tile = slot % tiles;
+  } else {
+    g = blockIdx.x / tiles;
+    tile = blockIdx.x % tiles;
+  }
   if (p.worker_steps != nullptr && p.step >= p.worker_steps[g]) return;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
-  __shared__ __attribute__((aligned(16))) E a_lds[TileShape<T, BM, AKIND>::kElems];
-  __shared__ __attribute__((aligned(16))) E b_lds[TileShape<T, BN, BKIND>::kElems];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // Two LDS stages of each operand tile; the weight-gradient product (one or two contraction
+  // tiles in all) keeps a single stage so that more workgroups fit on a compute unit.
+  constexpr int kStages = (AKIND == OP_TRANS && BKIND == OP_TRANS) ? 1 : 2;
+  E* const a_lds0 = reinterpret_cast<E*>(smem);
+  E* const b_lds0 = a_lds0 + kStages * A_ELEMS;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int lr32 = lane & 31, kb = lane >> 5;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
 
   const E* a_src = reinterpret_cast<const E*>(p.a) + (size_t)g * p.a_gs;
   const E* b_src = reinterpret_cast<const E*>(p.b) + (size_t)g * p.b_gs;
+  const size_t pg = (size_t)g * p.p_gs;
+  constexpr bool kIsDw = (AKIND == OP_TRANS && BKIND == OP_TRANS);   // weight-gradient product
+  const bool fused = kIsDw && (p.epi == EPI_DW_FUSED);
+
+  // Weight-update epilogue: start streaming the old weights now, they are not needed until
+  // the products are done.
+  float w_old[kIsDw ? TM : 1][kIsDw ? TN : 1][16];
+  if constexpr (kIsDw) if (fused) {
+    const float* wbase = p.params + pg + p.w_off;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
+          const int n = n0 + (wn * TN + j) * 32 + lr32;
+          const bool ok = m < p.M && n < p.N;
+          const float* wp = wbase + (ok ? (size_t)m * p.ldw + n : (size_t)0);
+          w_old[i][j][v] = p.streaming ? __builtin_nontemporal_load(wp) : *wp;
+        }
+  }
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -175,59 +248,116 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const bool bias_wg = (p.epi == EPI_DW_FUSED || p.epi == EPI_DW_GRAD) && blockIdx.x == 0;
+  const bool bias_wg = kIsDw && m0 == 0;
   float colsum = 0.0f;                       // db: thread n sums column n of the delta tile
 
-  for (int c0 = 0; c0 < p.Kc; c0 += BK) {
-    load_tile<T, BM, AKIND>(a_lds, a_src, p.lda, m0, p.M, c0, p.Kc, tid);
-    load_tile<T, BN, BKIND>(b_lds, b_src, p.ldb, n0, p.N, c0, p.Kc, tid);
-    __syncthreads();
+  // Software pipeline: two LDS stages, and two register sets so that the global loads of
+  // tiles it+1 and it+2 are both in flight while tile `it` is multiplied -- one tile of compute
+  // is shorter than the HBM latency it has to hide.
+  const int n_k = (p.Kc + BK - 1) / BK;
+  uint4 a_r0[IOA::NPT], b_r0[IOB::NPT], a_r1[IOA::NPT], b_r1[IOB::NPT];
+  uint32_t a_m0, b_m0, a_m1 = 0, b_m1 = 0;         // validity masks of the register sets
+  a_m0 = IOA::fetch(a_r0, a_src, p.lda, m0, p.M, 0, p.Kc, tid);
+  b_m0 = IOB::fetch(b_r0, b_src, p.ldb, n0, p.N, 0, p.Kc, tid);
+  IOA::stash(a_lds0, a_r0, a_m0, tid);
+  IOB::stash(b_lds0, b_r0, b_m0, tid);
+  // The weight-gradient product contracts over the minibatch only (one or two tiles): it keeps
+  // the plain one-tile prefetch and spends its registers on the streamed weights instead.
+  constexpr bool kDeep = !kIsDw;
+  if (kDeep && n_k > 1) {
+    a_m0 = IOA::fetch(a_r0, a_src, p.lda, m0, p.M, BK, p.Kc, tid);
+    b_m0 = IOB::fetch(b_r0, b_src, p.ldb, n0, p.N, BK, p.Kc, tid);
+  }
+  if (kDeep && n_k > 2) {
+    a_m1 = IOA::fetch(a_r1, a_src, p.lda, m0, p.M, 2 * BK, p.Kc, tid);
+    b_m1 = IOB::fetch(b_r1, b_src, p.ldb, n0, p.N, 2 * BK, p.Kc, tid);
+  }
+  __syncthreads();
+
+  // One pipeline step on tile `it`; (ra, rb) is the register set that holds tile it+1 and is
+  // refilled with tile it+3.  STEADY = all of tiles it+1 .. it+3 exist, so the step is
+  // straight-line code and the loads of the other register set can stay in flight across it.
+  auto compute = [&](int cur) {
+    const E* a_cur = a_lds0 + cur * A_ELEMS;
+    const E* b_cur = b_lds0 + cur * B_ELEMS;
 #pragma unroll
     for (int kk = 0; kk < BK / T::KSTEP; ++kk) {
       typename T::frag af[TM], bf[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int row = (wm * TM + i) * 32 + lr32;
-        if constexpr (T::kBf16) af[i] = load_frag_bf16<BM, AKIND>(a_lds, row, kk, kb);
-        else af[i] = load_frag_f32<BM, AKIND>(a_lds, row, kk, kb);
+        const int rb_ = (wm * TM + i) * 32;
+        if constexpr (T::kBf16) af[i] = load_frag_bf16<BM, AKIND>(a_cur, rb_, kk, lane);
+        else af[i] = load_frag_f32<BM, AKIND>(a_cur, rb_ + lr32, kk, kb);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int row = (wn * TN + j) * 32 + lr32;
-        if constexpr (T::kBf16) bf[j] = load_frag_bf16<BN, BKIND>(b_lds, row, kk, kb);
-        else bf[j] = load_frag_f32<BN, BKIND>(b_lds, row, kk, kb);
+        const int rb_ = (wn * TN + j) * 32;
+        if constexpr (T::kBf16) bf[j] = load_frag_bf16<BN, BKIND>(b_cur, rb_, kk, lane);
+        else bf[j] = load_frag_f32<BN, BKIND>(b_cur, rb_ + lr32, kk, kb);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = mfma(af[i], bf[j], acc[i][j]);
     }
-    if (BKIND == OP_TRANS && bias_wg && tid < BN) {
+    if (kIsDw && bias_wg && tid < BN) {
       // delta tile sits in LDS as [c][n]; rows beyond Kc were zero-filled
 #pragma unroll 8
-      for (int c = 0; c < BK; ++c) colsum += from_elem<T>(b_lds[c * BN + tid]);
+      for (int c = 0; c < BK; ++c) colsum += from_elem<T>(b_cur[c * IOB::STRIDE + tid]);
+    }
+  };
+  auto steady_step = [&](int it, uint4 (&ra)[IOA::NPT], uint4 (&rb)[IOB::NPT], uint32_t& ma, uint32_t& mb) {
+    const int cur = it & 1;
+    compute(cur);
+    IOA::stash(a_lds0 + (cur ^ 1) * A_ELEMS, ra, ma, tid);
+    IOB::stash(b_lds0 + (cur ^ 1) * B_ELEMS, rb, mb, tid);
+    ma = IOA::fetch(ra, a_src, p.lda, m0, p.M, (it + 3) * BK, p.Kc, tid);
+    mb = IOB::fetch(rb, b_src, p.ldb, n0, p.N, (it + 3) * BK, p.Kc, tid);
+    __syncthreads();
+  };
+  auto step = [&](int it, uint4 (&ra)[IOA::NPT], uint4 (&rb)[IOB::NPT], uint32_t& ma, uint32_t& mb) {
+    const int cur = it & 1;
+    compute(cur);
+    if (it + 1 < n_k) {
+      IOA::stash(a_lds0 + (cur ^ 1) * A_ELEMS, ra, ma, tid);
+      IOB::stash(b_lds0 + (cur ^ 1) * B_ELEMS, rb, mb, tid);
+    }
+    if (it + 3 < n_k) {
+      ma = IOA::fetch(ra, a_src, p.lda, m0, p.M, (it + 3) * BK, p.Kc, tid);
+      mb = IOB::fetch(rb, b_src, p.ldb, n0, p.N, (it + 3) * BK, p.Kc, tid);
     }
     __syncthreads();
+  };
+  if constexpr (kDeep) {
+    int it = 0;
+    for (; it + 4 < n_k; it += 2) {            // tiles it+3 and it+4 exist: no conditionals inside
+      steady_step(it, a_r0, b_r0, a_m0, b_m0);
+      steady_step(it + 1, a_r1, b_r1, a_m1, b_m1);
+    }
+    for (; it < n_k; it += 2) {                // drain (it stays even, so the sets keep their roles)
+      step(it, a_r0, b_r0, a_m0, b_m0);
+      if (it + 1 < n_k) step(it + 1, a_r1, b_r1, a_m1, b_m1);
+    }
+  } else {
+    for (int it = 0; it < n_k; ++it) {         // single LDS stage, next tile prefetched in registers
+      const bool more = it + 1 < n_k;
+      if (more) {
+        a_m0 = IOA::fetch(a_r0, a_src, p.lda, m0, p.M, (it + 1) * BK, p.Kc, tid);
+        b_m0 = IOB::fetch(b_r0, b_src, p.ldb, n0, p.N, (it + 1) * BK, p.Kc, tid);
+      }
+      compute(0);
+      if (more) {
+        __syncthreads();
+        IOA::stash(a_lds0, a_r0, a_m0, tid);
+        IOB::stash(b_lds0, b_r0, b_m0, tid);
+        __syncthreads();
+      }
+    }
   }
 
   // ---- epilogue: accumulator element v of lane (lr32, kb) is C[8*(v/4) + 4*kb + v%4][lr32] ----
-  const size_t pg = (size_t)g * p.p_gs;
-  if (p.epi == EPI_DW_FUSED || p.epi == EPI_DW_GRAD) {
-    const bool fused = (p.epi == EPI_DW_FUSED);
+  if constexpr (kIsDw) {
     float* wbase = (fused ? p.params : p.grads) + pg + p.w_off;
-    float w_old[TM][TN][16];
-    if (fused) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int m = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
-            const int n = n0 + (wn * TN + j) * 32 + lr32;
-            w_old[i][j][v] = (m < p.M && n < p.N) ? wbase[(size_t)m * p.ldw + n] : 0.0f;
-          }
-    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -240,8 +370,14 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
             const size_t off = (size_t)m * p.ldw + n;
             if (fused) {
               const float w_new = fmaf(-p.lr, acc[i][j][v], w_old[i][j][v]);
-              wbase[off] = w_new;
-              if (p.shadow != nullptr) p.shadow[pg + p.w_off + off] = f32_to_bf16_rne(w_new);
+              if (p.streaming) {
+                __builtin_nontemporal_store(w_new, wbase + off);
+                if (p.shadow != nullptr)
+                  __builtin_nontemporal_store(f32_to_bf16_rne(w_new), p.shadow + pg + p.w_off + off);
+              } else {
+                wbase[off] = w_new;
+                if (p.shadow != nullptr) p.shadow[pg + p.w_off + off] = f32_to_bf16_rne(w_new);
+              }
             } else {
               wbase[off] = acc[i][j][v];
             }
@@ -263,17 +399,28 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
 
   const float* bias = (p.epi == EPI_FWD_HIDDEN || p.epi == EPI_FWD_LOGITS)
                           ? p.params + pg + p.b_off : nullptr;
+  const E* aux = reinterpret_cast<const E*>(p.aux) + (size_t)g * p.aux_gs;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int n = n0 + (wn * TN + j) * 32 + lr32;
-      if (n >= p.out_cols) continue;
-      const float bn = bias != nullptr ? bias[n] : 0.0f;
+      const bool n_ok = n < p.out_cols;
+      const float bn = (bias != nullptr) ? bias[n_ok ? n : 0] : 0.0f;
+      // all loads of the tile first (they may not be reordered across the stores below)
+      float h[16];
+      if (p.epi == EPI_DX) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
+          const bool ok = n_ok && m < p.M;
+          h[v] = from_elem<T>(aux[ok ? (size_t)m * p.ldaux + n : (size_t)0]);
+        }
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int m = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
-        if (m >= p.M) continue;
+        if (!n_ok || m >= p.M) continue;
         const size_t o = (size_t)g * p.out_gs + (size_t)m * p.ldo + n;
         const float c = acc[i][j][v];
         if (p.epi == EPI_FWD_HIDDEN) {
@@ -281,30 +428,49 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
         } else if (p.epi == EPI_FWD_LOGITS) {
           reinterpret_cast<float*>(p.out)[o] = c + bn;
         } else {  // EPI_DX
-          const float h = from_elem<T>(
-              reinterpret_cast<const E*>(p.aux)[(size_t)g * p.aux_gs + (size_t)m * p.ldaux + n]);
-          reinterpret_cast<E*>(p.out)[o] = to_elem<T>(c * act_bwd_from_h(h, p.act));
+          reinterpret_cast<E*>(p.out)[o] = to_elem<T>(c * act_bwd_from_h(h[v], p.act));
         }
       }
     }
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND>
-static hipError_t launch_one(const GemmArgs& p, int n_groups, hipStream_t s) {
+static hipError_t launch_one(GemmArgs p, int n_groups, hipStream_t s) {
   if (p.M <= 0 || p.N <= 0 || n_groups <= 0) return hipSuccess;
-  dim3 grid((p.M + BM - 1) / BM, (p.N + BN - 1) / BN, n_groups);
-  hipLaunchKernelGGL((grouped_gemm_kernel<T, BM, BN, WM, WN, AKIND, BKIND>), grid, dim3(kThreads), 0,
-                     s, p);
+  using E = typename T::elem;
+  constexpr size_t kStages = (AKIND == OP_TRANS && BKIND == OP_TRANS) ? 1 : 2;
+  constexpr size_t kLds =
+      kStages * sizeof(E) * (TileShape<T, BM, AKIND>::kElems + TileShape<T, BN, BKIND>::kElems);
+  auto kernel = grouped_gemm_kernel<T, BM, BN, WM, WN, AKIND, BKIND>;
+  static bool configured = false;              // double-buffered tiles can exceed the 64 KB default
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  p.n_groups = n_groups;
+  const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles * n_groups)), dim3(kThreads), kLds, s, p);
   return hipGetLastError();
 }
 
+constexpr int kComputeUnits = 256;
+
 // Batch-row products (forward, backward-data): the whole minibatch sits in one M tile when
-// B <= 128 so that each weight element is read from HBM exactly once per product.
+// B <= 128 so that each weight element is read from HBM exactly once per product.  The wide
+// (128-column) tile halves LDS traffic per flop; it is used when it still yields at least one
+// workgroup per compute unit.
 template <typename T, int AKIND, int BKIND>
 static hipError_t launch_rows(const GemmArgs& p, int n_groups, hipStream_t s) {
   if (p.M <= 32) return launch_one<T, 32, 128, 1, 4, AKIND, BKIND>(p, n_groups, s);
-  if (p.M <= 64) return launch_one<T, 64, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
-  return launch_one<T, 128, 64, 4, 1, AKIND, BKIND>(p, n_groups, s);
+  const bool wide = (long)((p.N + 127) / 128) * n_groups * ((p.M + 127) / 128) >= kComputeUnits;
+  if (p.M <= 64) {
+    if (wide) return launch_one<T, 64, 128, 2, 2, AKIND, BKIND>(p, n_groups, s);
+    return launch_one<T, 64, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
+  }
+  if (wide) return launch_one<T, 128, 128, 2, 2, AKIND, BKIND>(p, n_groups, s);
+  return launch_one<T, 128, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
 }
 
 hipError_t launch_gemm_fwd(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s) {
@@ -316,8 +482,8 @@ hipError_t launch_gemm_dx(const GemmArgs& p, int n_groups, bool bf16, hipStream_
               : launch_rows<TF32, OP_CONTIG, OP_CONTIG>(p, n_groups, s);
 }
 hipError_t launch_gemm_dw(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s) {
-  return bf16 ? launch_one<TBF16, 128, 64, 4, 1, OP_TRANS, OP_TRANS>(p, n_groups, s)
-              : launch_one<TF32, 128, 64, 4, 1, OP_TRANS, OP_TRANS>(p, n_groups, s);
+  return bf16 ? launch_one<TBF16, 128, 64, 2, 2, OP_TRANS, OP_TRANS>(p, n_groups, s)
+              : launch_one<TF32, 128, 64, 2, 2, OP_TRANS, OP_TRANS>(p, n_groups, s);
 }
 
 }  // namespace prsgd

@@ -63,46 +63,49 @@ __global__ __launch_bounds__(kThreads) void sample_indices_kernel(int32_t* __res
   }
 }
 
-// Softmax cross-entropy head: one workgroup per worker, one wavefront per minibatch row.
-//   loss_i = -(1/B) sum_b log softmax(z_b)[c_b],   delta = (softmax(z) - onehot(c)) / B
+// Softmax cross-entropy head: one wavefront per minibatch row (4 rows per workgroup).
+//   row_loss[b] = -log softmax(z_b)[c_b],   delta = (softmax(z) - onehot(c)) / B
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ yb, void* __restrict__ delta,
-    float* __restrict__ losses, int batch, int n_classes, int ldc,
+    float* __restrict__ row_loss, int batch, int n_classes, int ldc,
     const int* __restrict__ worker_steps, int step) {
-  const int g = blockIdx.x;
+  const int g = blockIdx.y;
   if (worker_steps != nullptr && step >= worker_steps[g]) return;
-  __shared__ float row_loss[kMaxBatch];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.x * (kThreads / kWave) + wave;
+  if (b >= batch) return;
   const float inv_b = 1.0f / (float)batch;
-  for (int b = wave; b < batch; b += kThreads / kWave) {
-    const size_t r = (size_t)g * batch + b;
-    const float* z = logits + r * ldc;
-    float mx = -INFINITY;
-    for (int c = lane; c < n_classes; c += kWave) mx = fmaxf(mx, z[c]);
+  const size_t r = (size_t)g * batch + b;
+  const float* z = logits + r * ldc;
+  float mx = -INFINITY;
+  for (int c = lane; c < n_classes; c += kWave) mx = fmaxf(mx, z[c]);
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    float se = 0.0f;
-    for (int c = lane; c < n_classes; c += kWave) se += expf(z[c] - mx);
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  float se = 0.0f;
+  for (int c = lane; c < n_classes; c += kWave) se += expf(z[c] - mx);
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
-    const int label = yb[r];
-    for (int c = lane; c < ldc; c += kWave) {
-      float d = 0.0f;
-      if (c < n_classes) d = (expf(z[c] - mx) / se - (c == label ? 1.0f : 0.0f)) * inv_b;
-      if (BF16) reinterpret_cast<uint16_t*>(delta)[r * ldc + c] = f32_to_bf16_rne(d);
-      else reinterpret_cast<float*>(delta)[r * ldc + c] = d;
-    }
-    // an out-of-range label must not index outside the row
-    const float z_label = (label >= 0 && label < n_classes) ? z[label] : 0.0f;
-    if (lane == 0) row_loss[b] = (mx + logf(se)) - z_label;
+  for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
+  const int label = yb[r];
+  for (int c = lane; c < ldc; c += kWave) {
+    float d = 0.0f;
+    if (c < n_classes) d = (expf(z[c] - mx) / se - (c == label ? 1.0f : 0.0f)) * inv_b;
+    if (BF16) reinterpret_cast<uint16_t*>(delta)[r * ldc + c] = f32_to_bf16_rne(d);
+    else reinterpret_cast<float*>(delta)[r * ldc + c] = d;
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    float s = 0.0f;
-    for (int b = 0; b < batch; ++b) s += row_loss[b];
-    losses[g] = s * inv_b;
-  }
+  // an out-of-range label must not index outside the row
+  const float z_label = (label >= 0 && label < n_classes) ? z[label] : 0.0f;
+  if (lane == 0) row_loss[r] = (mx + logf(se)) - z_label;
+}
+
+// Minibatch loss of each worker: mean of its row losses, rows summed in slot order.
+__global__ void loss_mean_kernel(const float* __restrict__ row_loss, float* __restrict__ losses,
+                                 int n_workers, int batch) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_workers) return;
+  float s = 0.0f;
+  for (int b = 0; b < batch; ++b) s += row_loss[(size_t)g * batch + b];
+  losses[g] = s / (float)batch;
 }
 
 hipError_t launch_gather(const float* features, const int32_t* labels, void* xb, int32_t* yb,
@@ -130,15 +133,23 @@ hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long r
   return hipGetLastError();
 }
 
-hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* losses,
+hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
                                const int* worker_steps, int step, hipStream_t s) {
+  dim3 grid((batch + kThreads / kWave - 1) / (kThreads / kWave), n_workers);
   if (bf16)
-    hipLaunchKernelGGL(softmax_xent_kernel<true>, dim3(n_workers), dim3(kThreads), 0, s, logits, yb,
-                       delta, losses, batch, n_classes, ldc, worker_steps, step);
+    hipLaunchKernelGGL(softmax_xent_kernel<true>, grid, dim3(kThreads), 0, s, logits, yb, delta,
+                       row_loss, batch, n_classes, ldc, worker_steps, step);
   else
-    hipLaunchKernelGGL(softmax_xent_kernel<false>, dim3(n_workers), dim3(kThreads), 0, s, logits, yb,
-                       delta, losses, batch, n_classes, ldc, worker_steps, step);
+    hipLaunchKernelGGL(softmax_xent_kernel<false>, grid, dim3(kThreads), 0, s, logits, yb, delta,
+                       row_loss, batch, n_classes, ldc, worker_steps, step);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_mean(const float* row_loss, float* losses, int n_workers, int batch,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(loss_mean_kernel, dim3((n_workers + 63) / 64), dim3(64), 0, s, row_loss, losses,
+                     n_workers, batch);
   return hipGetLastError();
 }
 

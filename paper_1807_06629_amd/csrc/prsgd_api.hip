@@ -16,7 +16,8 @@ using namespace prsgd;
 namespace prsgd {
 const char* kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
-                                        "sgd_update", "average", "mean",       "broadcast", "lsq_steps"};
+                                        "sgd_update", "average", "mean",       "broadcast", "lsq_steps",
+                                        "mlp2_epoch"};
   return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
 }
 }  // namespace prsgd
@@ -29,7 +30,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local char g_init_error[256] = "";
 
 struct Carve {
-  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, shadow = 0, grads = 0, mean = 0, steps = 0;
+  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, steps = 0;
   size_t h[PRSGD_MAX_DIMS] = {0}, delta[PRSGD_MAX_DIMS] = {0};
   size_t total = 0;
 };
@@ -90,6 +91,7 @@ void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
   if (c->model == PRSGD_MLP) {
     const int L = lo.n_layers;
     cv->yb = take(n * b * 4);
+    cv->row_loss = take(n * b * 4);
     cv->xb = take(n * b * lo.ld[0] * es);
     for (int l = 1; l < L; ++l) {
       cv->h[l] = take(n * b * lo.ld[l] * es);
@@ -98,6 +100,12 @@ void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
     cv->delta[L] = take(n * b * lo.ld[L] * es);
     cv->logits = take(n * b * lo.ld[L] * 4);
     if (bf16) cv->shadow = take(n * (size_t)lo.m_pad * 2);
+    if (L == 2 && !bf16 && c->fused_update && (lo.d[1] % 16) == 0 && lo.d[2] <= 64 && c->batch <= 64) {
+      // epoch kernel: partial logits for the finest team split, arrival counters, abort flag
+      const size_t mr = ((size_t)c->batch + 15) / 16 * 16, d2p = ((size_t)lo.d[2] + 15) / 16 * 16;
+      cv->part = take(2 * n * (size_t)(lo.d[1] / 16) * mr * d2p * 4);
+      cv->sync = take((n + 1) * 128);
+    }
     if (!c->fused_update) cv->grads = take(n * (size_t)lo.m_pad * 4);
   }
   cv->total = off;
@@ -112,6 +120,9 @@ struct prsgd_ctx {
   Layout lo;
   Carve cv;
   bool bf16;
+  bool use_fused2;      // one-hidden-layer fp32 MLP: whole epochs in one cooperative launch
+  Fused2Plan f2;
+  bool streaming;       // replica set >= 1 GiB: weight traffic bypasses the last-level cache
   hipStream_t stream;
   const float* features;
   const void* targets;
@@ -213,6 +224,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
   base.shadow = ctx->shadow();
   base.p_gs = lo.m_pad;
   base.worker_steps = worker_steps;
+  base.streaming = ctx->streaming ? 1 : 0;
   base.step = step;
 
   auto act_in = [&](int l) -> const void* {   // H_l as stored (l = 0: the gathered batch)
@@ -238,7 +250,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
 
   LAUNCH(ctx, KK_LOSS,
          launch_softmax_xent(ctx->at<float>(cv.logits), ctx->at<int32_t>(cv.yb),
-                             ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.losses), N, B, lo.d[L],
+                             ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.row_loss), N, B, lo.d[L],
                              lo.ld[L], bf16, worker_steps, step, s));
 
   // backward: D_{l-1} needs the pre-update W_l, so it runs before layer l's weight kernel
@@ -273,6 +285,49 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
       LAUNCH(ctx, KK_UPDATE, launch_update_masked(ctx->params, ctx->grads(), ctx->shadow(), lo.m_pad,
                                                   N, ctx->lr, worker_steps, step, s));
   }
+  return PRSGD_OK;
+}
+
+Fused2Args fused2_args(prsgd_ctx* ctx, int k, const int* worker_steps) {
+  const prsgd_config& c = ctx->cfg;
+  const Layout& lo = ctx->lo;
+  Fused2Args a;
+  memset(&a, 0, sizeof(a));
+  a.features = ctx->features;
+  a.labels = reinterpret_cast<const int32_t*>(ctx->targets);
+  a.params = ctx->params;
+  a.m_pad = lo.m_pad;
+  a.w1_off = lo.w_off[0]; a.b1_off = lo.b_off[0]; a.w2_off = lo.w_off[1]; a.b2_off = lo.b_off[1];
+  a.ld1 = lo.ld[1]; a.ld2 = lo.ld[2];
+  a.n_workers = c.n_workers;
+  a.d0 = lo.d[0]; a.d1 = lo.d[1]; a.d2 = lo.d[2];
+  a.batch = c.batch;
+  a.rows = (long)c.rows_per_worker;
+  a.log2n = 0;
+  while ((1LL << a.log2n) < c.rows_per_worker) ++a.log2n;
+  a.act = c.activation;
+  a.lr = ctx->lr;
+  a.seed = c.seed;
+  a.t0 = (uint64_t)ctx->t;
+  a.k = k;
+  a.worker_steps = worker_steps;
+  a.part = ctx->at<float>(ctx->cv.part);
+  a.sync = ctx->at<unsigned int>(ctx->cv.sync);
+  a.row_loss = ctx->at<float>(ctx->cv.row_loss);
+  a.idx = ctx->at<int32_t>(ctx->cv.idx);
+  return a;
+}
+
+// The epoch kernel's bounded team barrier raises a flag instead of hanging; surface it.
+int check_fused2_abort(prsgd_ctx* ctx) {
+  if (!ctx->use_fused2) return PRSGD_OK;
+  unsigned int flag = 0;
+  hipError_t e = hipMemcpyAsync(&flag, ctx->at<unsigned int>(ctx->cv.sync) + (size_t)ctx->cfg.n_workers * 32,
+                                sizeof(flag), hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "abort-flag read");
+  if (flag != 0)
+    return set_err(ctx, PRSGD_ESTATE, "epoch kernel gave up waiting for a team member; parameters are invalid");
   return PRSGD_OK;
 }
 
@@ -350,7 +405,10 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   ctx->lo = lo;
   build_carve(cfg, lo, &ctx->cv);
   ctx->bf16 = cfg->model == PRSGD_MLP && cfg->gemm_dtype == PRSGD_BF16;
+  ctx->streaming = (size_t)cfg->n_workers * (size_t)lo.m_pad * sizeof(float) >= ((size_t)1 << 30);
   ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  ctx->use_fused2 = ctx->cv.part != 0 && ctx->cv.sync != 0 &&
+                    fused2_plan(cfg->n_workers, lo.d[0], lo.d[1], lo.d[2], cfg->batch, &ctx->f2);
   ctx->features = reinterpret_cast<const float*>(features_dev);
   ctx->targets = targets_dev;
   ctx->params = reinterpret_cast<float*>(params_dev);
@@ -402,6 +460,11 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
     ctx->t += k;
     return PRSGD_OK;
   }
+  if (ctx->use_fused2) {
+    if (k > 0) LAUNCH(ctx, KK_FUSED2, launch_fused2(ctx->f2, fused2_args(ctx, k, nullptr), ctx->stream));
+    ctx->t += k;
+    return PRSGD_OK;
+  }
   for (int32_t s = 0; s < k; ++s) {
     const int rc = mlp_step(ctx, ctx->t + 1, nullptr, 0);
     if (rc != PRSGD_OK) return rc;
@@ -434,6 +497,12 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
     ctx->t += k_max;
     return PRSGD_OK;
   }
+  if (ctx->use_fused2) {
+    if (k_max > 0)
+      LAUNCH(ctx, KK_FUSED2, launch_fused2(ctx->f2, fused2_args(ctx, k_max, steps_dev), ctx->stream));
+    ctx->t += k_max;
+    return PRSGD_OK;
+  }
   for (int32_t s = 0; s < k_max; ++s) {
     const int rc = mlp_step(ctx, ctx->t + 1, steps_dev, s);
     if (rc != PRSGD_OK) return rc;
@@ -445,7 +514,8 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
 int prsgd_average(prsgd_ctx* ctx) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   LAUNCH(ctx, KK_AVERAGE,
-         launch_average(ctx->params, ctx->shadow(), ctx->lo.m_pad, ctx->cfg.n_workers, ctx->stream));
+         launch_average(ctx->params, ctx->shadow(), ctx->lo.m_pad, ctx->cfg.n_workers, ctx->streaming,
+                        ctx->stream));
   return PRSGD_OK;
 }
 
@@ -472,6 +542,8 @@ int prsgd_read_params(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m)
   if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
   if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
   if (worker < -1 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
+  const int arc = check_fused2_abort(ctx);
+  if (arc != PRSGD_OK) return arc;
   const float* src;
   if (worker < 0) {
     LAUNCH(ctx, KK_MEAN, launch_mean(ctx->params, ctx->at<float>(ctx->cv.mean), ctx->lo.m_pad,
@@ -517,7 +589,12 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
 int prsgd_read_loss(prsgd_ctx* ctx, float* out_host) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
-  hipError_t e = hipMemcpyAsync(out_host, ctx->at<float>(ctx->cv.losses), sizeof(float) * ctx->cfg.n_workers,
+  hipError_t e = hipSuccess;
+  if (ctx->cfg.model == PRSGD_MLP)
+    e = launch_loss_mean(ctx->at<float>(ctx->cv.row_loss), ctx->at<float>(ctx->cv.losses),
+                         ctx->cfg.n_workers, ctx->cfg.batch, ctx->stream);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(out_host, ctx->at<float>(ctx->cv.losses), sizeof(float) * ctx->cfg.n_workers,
                                 hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_loss");
@@ -554,6 +631,15 @@ int prsgd_sgd_update(float* x_dev, const float* g_dev, uint16_t* shadow_dev, siz
     return set_err(nullptr, PRSGD_EINVAL, "prsgd_sgd_update: misaligned buffer");
   hipError_t e = launch_update(x_dev, g_dev, shadow_dev, count, lr, reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return hip_fail(nullptr, e, "prsgd_sgd_update");
+  return PRSGD_OK;
+}
+
+int prsgd_copy_bytes(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
+  if (dst_dev == nullptr || src_dev == nullptr || (bytes % 16) != 0 || ((uintptr_t)dst_dev % 16) != 0 ||
+      ((uintptr_t)src_dev % 16) != 0)
+    return set_err(nullptr, PRSGD_EINVAL, "prsgd_copy_bytes: bad argument");
+  hipError_t e = launch_copy(dst_dev, src_dev, bytes, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(nullptr, e, "prsgd_copy_bytes");
   return PRSGD_OK;
 }
 

@@ -43,7 +43,9 @@ struct GemmArgs {
   const void* a; long a_gs; int lda;
   const void* b; long b_gs; int ldb;
   int M, N, Kc;
+  int n_groups;                       // filled in by the launcher
   int epi;
+  int streaming;                      // weights far exceed the caches: non-temporal accesses
   int act;                            // PRSGD_TANH | PRSGD_RELU
   float lr;
   // parameters / gradients (fp32, replica stride m_pad), bf16 shadow of the parameters
@@ -58,8 +60,28 @@ struct GemmArgs {
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
-  KK_LSQ, KK_COUNT
+  KK_LSQ, KK_FUSED2, KK_COUNT
 };
+
+// Epoch kernel for fp32 MLPs with one hidden layer (kernels_fused2.hip).
+struct Fused2Plan {
+  int KBI, NT, MT;     // template shape: W_1 row blocks per wavefront, hidden tiles, batch tiles
+  int P;               // workgroups per worker
+  int d2p, ldx;        // padded class count, LDS row stride of the gathered batch
+};
+struct Fused2Args {
+  const float* features; const int32_t* labels;
+  float* params; long m_pad; long w1_off, b1_off, w2_off, b2_off; int ld1, ld2;
+  int n_workers, P, d0, d1, d2, d2p, ldx, batch; long rows; int log2n;
+  int act; float lr; uint64_t seed; uint64_t t0; int k;
+  const int* worker_steps;       // Algorithm 3 step counts (nullptr: every worker takes k steps)
+  float* part;                   // [2][N][P][MT*16][d2p] partial logits
+  unsigned int* sync;            // [N][32] arrival counters (+ launch base), then the abort flag
+  float* row_loss; int32_t* idx;
+};
+size_t fused2_lds_bytes(const Fused2Plan& pl);
+bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* pl);
+hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s);
 const char* kernel_kind_name(int kind);
 
 // ---- launchers (each returns the hipError_t of the launch) --------------------------------
@@ -73,15 +95,19 @@ hipError_t launch_gather(const float* features, const int32_t* labels, void* xb,
                          hipStream_t s);
 hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long rows, int64_t t_first,
                                  int n_steps, int32_t* out, hipStream_t s);
-hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* losses,
+hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
                                const int* worker_steps, int step, hipStream_t s);
+hipError_t launch_loss_mean(const float* row_loss, float* losses, int n_workers, int batch,
+                            hipStream_t s);
 
-hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, hipStream_t s);
+hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, bool streaming,
+                          hipStream_t s);
 hipError_t launch_mean(const float* params, float* out, long m_pad, int n_workers, hipStream_t s);
 hipError_t launch_broadcast(const float* src, float* params, uint16_t* shadow, long m_pad,
                             int n_workers, hipStream_t s);
 hipError_t launch_refresh_shadow(const float* params, uint16_t* shadow, long count, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t count, float lr,
                          hipStream_t s);
 hipError_t launch_update_masked(float* x, const float* g, uint16_t* shadow, long m_pad, int n_workers,

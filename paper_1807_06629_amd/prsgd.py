@@ -73,6 +73,7 @@ def _load() -> ctypes.CDLL:
         "prsgd_read_indices": (ctypes.c_int, [vp, vp]),
         "prsgd_sample_indices": (ctypes.c_int, [ctypes.c_uint64, i32, i32, i64, i64, i32, vp, vp]),
         "prsgd_sgd_update": (ctypes.c_int, [vp, vp, vp, sz, ctypes.c_float, vp]),
+        "prsgd_copy_bytes": (ctypes.c_int, [vp, vp, sz, vp]),
         "prsgd_set_lr": (ctypes.c_int, [vp, ctypes.c_float]),
         "prsgd_set_iteration": (ctypes.c_int, [vp, i64]),
         "prsgd_iteration": (i64, [vp]),
@@ -251,6 +252,15 @@ def prsgd_sgd_update(x: torch.Tensor, g: torch.Tensor, lr: float,
         s = torch.cuda.current_stream(x.device)
         _check(_lib.prsgd_sgd_update(x.data_ptr(), g.data_ptr(), sp, x.numel(), float(lr),
                                      _stream_ptr(s)))
+
+
+def prsgd_copy_bytes(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (dst.is_cuda and src.is_cuda):
+        raise ValueError("dst and src must be device tensors of equal byte size")
+    with torch.cuda.device(src.device):
+        s = torch.cuda.current_stream(src.device)
+        _check(_lib.prsgd_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(s)))
 
 
 def prsgd_set_lr(h: Handle, lr: float) -> None:

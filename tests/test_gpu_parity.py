@@ -156,6 +156,74 @@ def test_c4_shape_interval_sweep_reduced_horizon(P, D):
         P.prsgd_destroy(h)
 
 
+# --------------------------------------------------------------------------- epoch kernel (one hidden layer, fp32)
+EPOCH_SHAPES = [
+    dict(dims=(64, 32, 10), batch=8, n_workers=3),                 # P=2 teams, N not a multiple of 8
+    dict(dims=(100, 48, 7), batch=20, n_workers=8),                # ragged d0 (7 row blocks), two batch tiles
+    dict(dims=(256, 128, 10), batch=8, n_workers=16),              # C4's shape
+    dict(dims=(784, 256, 10), batch=32, n_workers=8),              # C2's shape
+    dict(dims=(128, 64, 33), batch=50, n_workers=2),               # 33 classes (padded to 48), four batch tiles
+    dict(dims=(1024, 16, 3), batch=1, n_workers=1),                # widest input, B = 1, single-member team
+]
+
+
+def _kernel_names(P, h, k, interval):
+    P.prsgd_profile_enable(h, True)
+    P.prsgd_run(h, k, interval)
+    names = {r["name"] for r in P.prsgd_profile_read(h)}
+    P.prsgd_profile_enable(h, False)
+    return names
+
+
+@pytest.mark.parametrize("shape", EPOCH_SHAPES)
+@pytest.mark.parametrize("activation", ["tanh", "relu"])
+def test_epoch_kernel_parity(P, D, shape, activation):
+    w = small_mlp(activation=activation, rows_per_worker=128, interval=4, iterations=12, lr=0.02,
+                  **shape)
+    inp = inputs_for(w)
+    h = _open(D, w, inp)
+    P.prsgd_local_steps(h, 1)
+    one = oracle_run(w, inp, iterations=1)
+    assert rel_err(D.read_all(h), one["x"]) <= ONE_STEP_TOL
+    assert np.allclose(P.prsgd_read_loss(h), one["losses"], rtol=2e-5, atol=1e-6)
+    assert np.array_equal(P.prsgd_read_indices(h)[0],
+                          oracle.sample_rows(w.index_seed, 0, 1, w.batch, w.rows_per_worker))
+    names = _kernel_names(P, h, w.iterations - 1, w.interval)
+    assert "mlp2_epoch" in names and "gemm_fwd" not in names      # the fused path really ran
+    want = oracle_run(w, inp)
+    assert rel_err(D.read_all(h), want["x"]) <= 1e-4
+    assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=1e-3, atol=1e-6)
+    P.prsgd_destroy(h)
+
+
+def test_epoch_kernel_matches_layerwise_kernels(P, D):
+    # same problem through the fused epoch kernel and through the per-layer kernel chain
+    w = small_mlp(dims=(96, 32, 10), batch=16, n_workers=8, rows_per_worker=128, interval=5,
+                  iterations=15, activation="tanh")
+    inp = inputs_for(w)
+    outs = []
+    for fused in (True, False):           # the un-fused update path never uses the epoch kernel
+        h = _open(D, w, inp, fused_update=fused)
+        P.prsgd_run(h, w.iterations, w.interval)
+        outs.append(D.read_all(h))
+        P.prsgd_destroy(h)
+    assert rel_err(outs[0], outs[1]) <= 1e-5
+
+
+def test_epoch_kernel_heterogeneous_steps(P, D):
+    w = small_mlp(dims=(64, 32, 10), batch=8, n_workers=4, rows_per_worker=128)
+    inp = inputs_for(w)
+    steps = [5, 3, 0, 1]
+    h = _open(D, w, inp)
+    D.run_algorithm3(h, steps, 3)
+    args = oracle_args(w, inp)
+    args.pop("bf16")
+    want = oracle.run_heterogeneous(**args, lr=w.lr, worker_steps=steps, n_epochs=3)
+    assert P.prsgd_iteration(h) == want["t"]
+    assert rel_err(D.read_all(h), want["x"]) <= 1e-4
+    P.prsgd_destroy(h)
+
+
 # --------------------------------------------------------------------------- MLP, bf16 operands
 @pytest.mark.parametrize("shape", [
     dict(dims=(96, 80, 40, 10), batch=64, n_workers=4),
