@@ -118,13 +118,28 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       ylab[tid] = lab[r];
     }
     __syncthreads();
-    // (b) gather the rows into LDS (16-byte vectors; d0 is a multiple of 4)
+    // (b) gather the rows into LDS (16-byte vectors; d0 is a multiple of 4).  Eight loads per
+    // thread are issued before the first is consumed so that their HBM latencies overlap.
     {
-      const int v4 = d0 >> 2;
-      for (int e = tid; e < B * v4; e += kThreads) {
-        const int r = e / v4, c = e - r * v4;
-        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
-        *reinterpret_cast<f32x4_t*>(X + (size_t)r * ldx + 4 * c) = v;
+      constexpr int G = 8;
+      const int v4 = d0 >> 2, total = B * v4;
+      for (int e0 = 0; e0 < total; e0 += G * kThreads) {
+        f32x4_t v[G];
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          const int e = e0 + u * kThreads + tid;
+          const int ec = e < total ? e : 0;
+          const int r = ec / v4, c = ec - r * v4;
+          v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
+        }
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          const int e = e0 + u * kThreads + tid;
+          if (e < total) {
+            const int r = e / v4, c = e - r * v4;
+            *reinterpret_cast<f32x4_t*>(X + (size_t)r * ldx + 4 * c) = v[u];
+          }
+        }
       }
     }
     __syncthreads();
@@ -172,36 +187,51 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       float sum = 0.0f;
 #pragma unroll 8
       for (int n = 0; n < W; ++n) sum = fmaf(h[b * W + n], w2[n * D2P + c], sum);
-      my_part[e] = sum;
+      // agent-scope store: visible to the other compute units without flushing whole caches
+      __hip_atomic_store(my_part + e, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // (e) team barrier: arrivals are counted in HBM; the wait is bounded
-    __threadfence();
+    // (e) team barrier: arrivals are counted in HBM; the wait is bounded.  The partials were
+    // written with agent-scope stores; draining this wavefront's stores before the workgroup
+    // barrier orders them before the arrival count without a cache-wide release fence.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-      __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const unsigned target = base + (unsigned)p.P * (unsigned)s;
       unsigned spins = 0;
       int bad = 0;
-      while ((int)(__hip_atomic_load(cnt, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+      while ((int)(__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
         if (++spins > kSpinLimit ||
             __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
           __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           bad = 1;
           break;
         }
-        __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_s_sleep(1);
       }
       flag[0] = bad;
     }
     __syncthreads();
-    __threadfence();
     if (flag[0] != 0) { aborted = true; break; }
     // (f) logits = b_2 + sum of the P partials in member order; softmax cross-entropy head
     {
       const float* team_part = p.part + (((size_t)(s & 1) * p.n_workers + i) * p.P) * part_team;
       for (int e = tid; e < MR * D2P; e += kThreads) {
         float sum = b2[e % D2P];
-        for (int jj = 0; jj < p.P; ++jj) sum += team_part[(size_t)jj * part_team + e];
+        // agent-scope loads (never a stale cached copy), eight in flight at a time; the sum
+        // itself runs in member order
+        for (int j0 = 0; j0 < p.P; j0 += 8) {
+          float v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int jj = j0 + u < p.P ? j0 + u : 0;
+            v[u] = __hip_atomic_load(team_part + (size_t)jj * part_team + e, __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (j0 + u < p.P) sum += v[u];
+        }
         lg[e] = sum;
       }
     }

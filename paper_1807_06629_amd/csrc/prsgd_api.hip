@@ -102,7 +102,9 @@ void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
     if (bf16) cv->shadow = take(n * (size_t)lo.m_pad * 2);
     if (L == 2 && !bf16 && c->fused_update && (lo.d[1] % 16) == 0 && lo.d[2] <= 64 && c->batch <= 64) {
       // epoch kernel: partial logits for the finest team split, arrival counters, abort flag
-      const size_t mr = ((size_t)c->batch + 15) / 16 * 16, d2p = ((size_t)lo.d[2] + 15) / 16 * 16;
+      // batch tiles come in 1, 2 or 4 blocks of 16 rows
+      const size_t mr = c->batch <= 16 ? 16 : c->batch <= 32 ? 32 : 64;
+      const size_t d2p = ((size_t)lo.d[2] + 15) / 16 * 16;
       cv->part = take(2 * n * (size_t)(lo.d[1] / 16) * mr * d2p * 4);
       cv->sync = take((n + 1) * 128);
     }
