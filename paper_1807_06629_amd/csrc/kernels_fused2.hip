@@ -394,9 +394,10 @@ hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s) {
   args.d2p = pl.d2p;
   args.ldx = pl.ldx;
   void* kargs[] = {&args};
-  // cooperative launch: the runtime refuses a grid that cannot be fully resident
-  return hipLaunchCooperativeKernel(sym, dim3((unsigned)(args.n_workers * pl.P)), dim3(kThreads), kargs,
-                                    (unsigned)fused2_lds_bytes(pl), s);
+  // Plain launch: fused2_plan has checked that the whole grid fits on the device at once, and a
+  // team member that never shows up ends in the kernel's bounded wait, not in a hang.
+  return hipLaunchKernel(sym, dim3((unsigned)(args.n_workers * pl.P)), dim3(kThreads), kargs,
+                         fused2_lds_bytes(pl), s);
 }
 
 }  // namespace prsgd

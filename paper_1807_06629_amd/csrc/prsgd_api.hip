@@ -122,7 +122,7 @@ struct prsgd_ctx {
   Layout lo;
   Carve cv;
   bool bf16;
-  bool use_fused2;      // one-hidden-layer fp32 MLP: whole epochs in one cooperative launch
+  bool use_fused2;      // one-hidden-layer fp32 MLP: whole epochs in one launch
   Fused2Plan f2;
   bool streaming;       // replica set >= 1 GiB: weight traffic bypasses the last-level cache
   hipStream_t stream;
