@@ -50,9 +50,11 @@ def test_parameter_counts_match_the_closed_form(P):
 
 
 def test_workspace_grows_with_shadow_and_gradient_buffers(P):
-    f32 = P.make_config(2, "mlp", (64, 32, 10), 8, 64, 0.1, 1, "relu", "f32", True)
-    bf = P.make_config(2, "mlp", (64, 32, 10), 8, 64, 0.1, 1, "relu", "bf16", True)
-    unf = P.make_config(2, "mlp", (64, 32, 10), 8, 64, 0.1, 1, "relu", "f32", False)
+    # two hidden layers: no epoch-kernel buffers, so the only differences are the ones named
+    dims = (64, 32, 24, 10)
+    f32 = P.make_config(2, "mlp", dims, 8, 64, 0.1, 1, "relu", "f32", True)
+    bf = P.make_config(2, "mlp", dims, 8, 64, 0.1, 1, "relu", "bf16", True)
+    unf = P.make_config(2, "mlp", dims, 8, 64, 0.1, 1, "relu", "f32", False)
     stride = P.prsgd_param_stride(f32)
     assert P.prsgd_workspace_bytes(unf) - P.prsgd_workspace_bytes(f32) >= 2 * stride * 4
     assert P.prsgd_workspace_bytes(bf) > 0
