@@ -9,8 +9,9 @@
 //     MFMA B-operand registers of the forward product are, element for element, the accumulator
 //     registers of the weight-gradient product: eq. (3) for W_1 is a register-to-register fma;
 //   - its slices of b_1 and W_2 (and a private copy of b_2) live in LDS;
-//   - per iteration it draws the minibatch rows, gathers them into LDS, computes its slice of the
-//     hidden layer, and contributes a partial logit block.  One team-wide barrier per iteration
+//   - per iteration it computes its slice of the hidden layer on the minibatch held in LDS and
+//     contributes a partial logit block; the next iteration's rows are drawn and gathered
+//     (HBM -> registers) meanwhile.  One team-wide barrier per iteration
 //     (a counter in HBM, bounded spin) lets every member sum the P partials in fixed order;
 //     everything after that (softmax, both delta blocks, dW_2, db, dW_1) is local to the slice.
 // Teams of different workers never synchronise.  Summation orders are fixed, so a run is
@@ -20,8 +21,10 @@
 namespace prsgd {
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr unsigned kSpinLimit = 1u << 22;     // bounded wait: a lost team member aborts the launch
+constexpr int kAgentScope = 16;               // buffer-load cache policy: the sc1 bit (agent scope)
 
 __device__ __forceinline__ f32x4_t mfma16(float a, float b, f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -72,9 +75,10 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   float* w2 = lg + MR * D2P;                               // [W][D2P]
   float* b1 = w2 + W * D2P;                                // [W]
   float* b2 = b1 + W;                                      // [D2P]
-  int* rows = reinterpret_cast<int*>(b2 + D2P);            // [MR]
-  int* ylab = rows + MR;                                   // [MR]
-  int* flag = ylab + MR;                                   // [1] abort broadcast
+  int* rows = reinterpret_cast<int*>(b2 + D2P);            // [MR] rows of this iteration
+  int* ylab = rows + MR;                                   // [MR] their labels
+  int* rows_next = ylab + MR;                              // [MR] rows of the next iteration
+  int* flag = rows_next + MR;                              // [1] abort broadcast
 
   float* prm = p.params + (size_t)i * p.m_pad;
   const float* feat = p.features + (size_t)i * p.rows * d0;
@@ -109,61 +113,124 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   const size_t part_team = (size_t)MR * D2P;                      // floats per (team member)
   bool aborted = false;
 
-  for (int s = 1; s <= my_k; ++s) {
-    const uint64_t t = p.t0 + (uint64_t)s;
-    // (a) minibatch rows of this iteration
-    if (tid < B) {
-      const int r = sample_row(p.seed, (uint32_t)i, t, (uint32_t)tid, p.log2n);
-      rows[tid] = r;
-      ylab[tid] = lab[r];
+  // ---- minibatch pipeline ----------------------------------------------------------------------
+  // The index stream is a pure function of (seed, worker, iteration, slot): the rows of iteration
+  // s+1 are drawn at the start of iteration s and their features travel HBM -> registers while
+  // iteration s computes; they are written to LDS once X is no longer read.  A thread owns the
+  // 16-byte column pc of rows rg, rg + ng, rg + 2 ng, ... (a row is at most 256 vectors wide).
+  // Rows B .. MR-1 of X receive a copy of the first drawn row: finite values that only ever meet
+  // zero deltas.
+  constexpr int PF = MT <= 2 ? 16 * MT : 0;                // vectors per thread; 0 = no prefetch
+  const int v4 = d0 >> 2, total4 = B * v4;
+  int cw_log = 4;                                          // ng <= 16 divides MR
+  while ((1 << cw_log) < v4) ++cw_log;
+  const int pc = tid & ((1 << cw_log) - 1), ng = kThreads >> cw_log;
+  const bool pc_ok = pc < v4;
+  int rg = tid >> cw_log;
+  f32x4_t pre[PF > 0 ? PF : 1];
+  auto gather_issue = [&](const int* rws) {
+    // opaque copy: keeps the per-vector addresses and predicates from being hoisted out of the
+    // iteration loop into (spilled) registers
+    asm volatile("" : "+v"(rg));
+    const float* src = feat + (pc_ok ? 4 * pc : 0);
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      if (ng * u < B) {                                    // uniform over the workgroup
+        const int r = rg + ng * u;
+        pre[u] = *reinterpret_cast<const f32x4_t*>(src + (size_t)rws[r < B ? r : 0] * d0);
+      }
     }
-    __syncthreads();
-    // (b) gather the rows into LDS (16-byte vectors; d0 is a multiple of 4).  Eight loads per
-    // thread are issued before the first is consumed so that their HBM latencies overlap.
-    {
-      constexpr int G = 8;
-      const int v4 = d0 >> 2, total = B * v4;
-      for (int e0 = 0; e0 < total; e0 += G * kThreads) {
-        f32x4_t v[G];
+  };
+  auto gather_store = [&]() {
+    asm volatile("" : "+v"(rg));
+    if (pc_ok) {
+      float* dst = X + (size_t)rg * ldx + 4 * pc;
+      const int step = ng * ldx;
 #pragma unroll
-        for (int u = 0; u < G; ++u) {
-          const int e = e0 + u * kThreads + tid;
-          const int ec = e < total ? e : 0;
-          const int r = ec / v4, c = ec - r * v4;
-          v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
-        }
+      for (int u = 0; u < PF; ++u) {
+        if (ng * u < B) *reinterpret_cast<f32x4_t*>(dst) = pre[u];
+        dst += step;
+      }
+    }
+  };
+  // Gather without the register stage (shapes whose minibatch does not fit the register budget).
+  auto gather_direct = [&]() {
+    constexpr int G = 8;
+    for (int e0 = 0; e0 < total4; e0 += G * kThreads) {
+      f32x4_t v[G];
 #pragma unroll
-        for (int u = 0; u < G; ++u) {
-          const int e = e0 + u * kThreads + tid;
-          if (e < total) {
-            const int r = e / v4, c = e - r * v4;
-            *reinterpret_cast<f32x4_t*>(X + (size_t)r * ldx + 4 * c) = v[u];
-          }
+      for (int u = 0; u < G; ++u) {
+        const int e = e0 + u * kThreads + tid;
+        const int ec = e < total4 ? e : 0;
+        const int r = ec / v4, c = ec - r * v4;
+        v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
+      }
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const int e = e0 + u * kThreads + tid;
+        if (e < total4) {
+          const int r = e / v4, c = e - r * v4;
+          *reinterpret_cast<f32x4_t*>(X + (size_t)r * ldx + 4 * c) = v[u];
         }
       }
     }
-    __syncthreads();
-    // (c) forward slice: contraction index of MFMA step s is k = 16 kb + 4 q4 + s
+  };
+
+  // rows, labels and features of the first iteration
+  if (tid < B) {
+    const int r = sample_row(p.seed, (uint32_t)i, p.t0 + 1, (uint32_t)tid, p.log2n);
+    rows[tid] = r;
+    ylab[tid] = lab[r];
+  }
+  __syncthreads();
+  if constexpr (PF > 0) { gather_issue(rows); gather_store(); } else { gather_direct(); }
+  __syncthreads();
+
+  // partial-logit exchange: Q 16-byte vectors per member; G groups of members are summed in
+  // parallel (group g = members [g * PG, (g+1) * PG) in order), then the groups in order
+  const int Q = MR * D2P / 4;
+  const int G = Q < kThreads ? kThreads / Q : 1;
+  const int PG = (p.P + G - 1) / G;
+
+  for (int s = 1; s <= my_k; ++s) {
+    // (a) draw the rows of iteration s+1 (read back from LDS several barriers later)
+    int lab_next = 0;
+    if (PF > 0 && s < my_k && tid < B) {
+      const int r = sample_row(p.seed, (uint32_t)i, p.t0 + (uint64_t)s + 1, (uint32_t)tid, p.log2n);
+      rows_next[tid] = r;
+      lab_next = lab[r];
+    }
+    // (c) forward slice: contraction index of MFMA step q is k = 16 kb + 4 q4 + q.  Row blocks
+    // past the last one hold zero weights and re-read the last block, so the loop is branch-free.
     {
       f32x4_t acc[MT][NT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+      // the A fragments of row block kbi+1 are read from LDS while block kbi is multiplied; the
+      // scheduling fence keeps the compiler from hoisting every block's reads (and their
+      // registers) to the top
+      auto load_a = [&](int kbi, f32x4_t (&a)[MT]) {
+        const int kb = min(wave + 4 * kbi, KB - 1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          a[mt] = *reinterpret_cast<const f32x4_t*>(X + (size_t)(mt * 16 + n16) * ldx + 16 * kb + 4 * q4);
+      };
+      f32x4_t a_cur[MT], a_nxt[MT];
+      load_a(0, a_cur);
 #pragma unroll
       for (int kbi = 0; kbi < KBI; ++kbi) {
-        const int kb = wave + 4 * kbi;
-        if (kb < KB) {
+        if (kbi + 1 < KBI) load_a(kbi + 1, a_nxt);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const f32x4_t a4 =
-                *reinterpret_cast<const f32x4_t*>(X + (size_t)(mt * 16 + n16) * ldx + 16 * kb + 4 * q4);
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+          for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-              for (int q = 0; q < 4; ++q) acc[mt][nt] = mfma16(a4[q], w1[kbi][nt][q], acc[mt][nt]);
-          }
-        }
+            for (int q = 0; q < 4; ++q) acc[mt][nt] = mfma16(a_cur[mt][q], w1[kbi][nt][q], acc[mt][nt]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a_cur[mt] = a_nxt[mt];
       }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
@@ -213,43 +280,85 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
     }
     __syncthreads();
     if (flag[0] != 0) { aborted = true; break; }
-    // (f) logits = b_2 + sum of the P partials in member order; softmax cross-entropy head
+    // (f) sum the P partial blocks.  The other members wrote them through to the coherence
+    // point; reading them with agent-scope (sc1) 16-byte buffer loads never returns a copy
+    // cached before the arrivals just observed, and needs no cache-wide invalidate.
     {
       const float* team_part = p.part + (((size_t)(s & 1) * p.n_workers + i) * p.P) * part_team;
-      for (int e = tid; e < MR * D2P; e += kThreads) {
-        float sum = b2[e % D2P];
-        // agent-scope loads (never a stale cached copy), eight in flight at a time; the sum
-        // itself runs in member order
-        for (int j0 = 0; j0 < p.P; j0 += 8) {
-          float v[8];
+      const __amdgpu_buffer_rsrc_t team_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<float*>(team_part), 0, (int)(p.P * part_team * sizeof(float)), 0x00020000);
+      float* lgp = red;                                    // [G][MR * D2P] group sums
+      for (int w0 = tid; w0 < G * Q; w0 += kThreads) {     // one pass when Q <= 256
+        const int g = w0 / Q, q = w0 - g * Q;
+        const int j_lo = g * PG, j_hi = min(p.P, j_lo + PG);
+        f32x4_t sum = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+        for (int j0 = j_lo; j0 < j_hi; j0 += 8) {
+          u32x4_t v[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
-            const int jj = j0 + u < p.P ? j0 + u : 0;
-            v[u] = __hip_atomic_load(team_part + (size_t)jj * part_team + e, __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
+            const int jj = j0 + u < j_hi ? j0 + u : j_lo;
+            v[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                team_rsrc, (int)((jj * part_team + 4 * q) * sizeof(float)), 0, kAgentScope);
           }
 #pragma unroll
           for (int u = 0; u < 8; ++u)
-            if (j0 + u < p.P) sum += v[u];
+            if (j0 + u < j_hi) sum += __builtin_bit_cast(f32x4_t, v[u]);
         }
-        lg[e] = sum;
+        *reinterpret_cast<f32x4_t*>(lgp + (size_t)g * MR * D2P + 4 * q) = sum;
       }
     }
+    // the partials are in: start the next minibatch's features towards the registers
+    if constexpr (PF > 0) {
+      if (s < my_k) gather_issue(rows_next);
+    }
     __syncthreads();
-    if (tid < MR) {
-      float* row = lg + tid * D2P;
-      if (tid < B) {
-        float mx = -INFINITY;
-        for (int c = 0; c < d2; ++c) mx = fmaxf(mx, row[c]);
-        float se = 0.0f;
-        for (int c = 0; c < d2; ++c) se += expf(row[c] - mx);
-        const int y = ylab[tid];
-        const float zy = (y >= 0 && y < d2) ? row[y] : 0.0f;
-        if (j == 0) p.row_loss[(size_t)i * B + tid] = (mx + logf(se)) - zy;
-        for (int c = 0; c < D2P; ++c)
-          row[c] = c < d2 ? (expf(row[c] - mx) / se - (c == y ? 1.0f : 0.0f)) * inv_b : 0.0f;
-      } else {
-        for (int c = 0; c < D2P; ++c) row[c] = 0.0f;
+    // logits = b_2 + group sums in order; softmax cross-entropy head, 16 lanes per minibatch
+    // row, lane l holding classes l, l + 16, l + 32, l + 48 (d_2 <= 64)
+    {
+      const float* lgp = red;
+      const int l16 = tid & 15;
+      for (int b = tid >> 4; b < MR; b += kThreads / 16) {
+        float* row = lg + b * D2P;
+        if (b < B) {
+          float z[4];
+          float mx = -INFINITY;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int c = l16 + 16 * q;
+            z[q] = -INFINITY;
+            if (c < d2) {
+              float sum = b2[c];
+              for (int g = 0; g < G; ++g) sum += lgp[(size_t)g * MR * D2P + b * D2P + c];
+              z[q] = sum;
+              mx = fmaxf(mx, sum);
+            }
+          }
+#pragma unroll
+          for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 16));
+          float ex[4];
+          float se = 0.0f;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            ex[q] = (l16 + 16 * q < d2) ? expf(z[q] - mx) : 0.0f;
+            se += ex[q];
+          }
+#pragma unroll
+          for (int o = 8; o > 0; o >>= 1) se += __shfl_xor(se, o, 16);
+          const int y = ylab[b];
+          const bool y_ok = y >= 0 && y < d2;               // an out-of-range label selects nothing
+          if (j == 0 && l16 == (y_ok ? (y & 15) : 0)) {
+            const int yq = y_ok ? (y >> 4) : 0;
+            const float zy = !y_ok ? 0.0f : yq == 0 ? z[0] : yq == 1 ? z[1] : yq == 2 ? z[2] : z[3];
+            p.row_loss[(size_t)i * B + b] = (mx + logf(se)) - zy;
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int c = l16 + 16 * q;
+            if (c < D2P) row[c] = c < d2 ? (ex[q] / se - (c == y ? 1.0f : 0.0f)) * inv_b : 0.0f;
+          }
+        } else {
+          for (int c = l16; c < D2P; c += 16) row[c] = 0.0f;
+        }
       }
     }
     __syncthreads();
@@ -257,24 +366,32 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
     for (int e = tid; e < MR * W; e += kThreads) {
       const int b = e / W, n = e % W;
       float sum = 0.0f;
-      for (int c = 0; c < D2P; ++c) sum = fmaf(lg[b * D2P + c], w2[n * D2P + c], sum);
+      for (int c = 0; c < D2P; c += 4) {
+        const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(lg + b * D2P + c);
+        const f32x4_t w4 = *reinterpret_cast<const f32x4_t*>(w2 + n * D2P + c);
+        sum = fmaf(d4.x, w4.x, sum); sum = fmaf(d4.y, w4.y, sum);
+        sum = fmaf(d4.z, w4.z, sum); sum = fmaf(d4.w, w4.w, sum);
+      }
       dl1[e] = sum * act2_bwd(h[e], p.act);
     }
     __syncthreads();
     for (int e = tid; e < W * D2P; e += kThreads) {
       const int n = e / D2P, c = e % D2P;
       float sum = 0.0f;
+#pragma unroll 8
       for (int b = 0; b < B; ++b) sum = fmaf(h[b * W + n], lg[b * D2P + c], sum);
       w2[e] = fmaf(-p.lr, sum, w2[e]);
     }
     if (tid < D2P) {
       float sum = 0.0f;
+#pragma unroll 8
       for (int b = 0; b < B; ++b) sum += lg[b * D2P + tid];
       b2[tid] = fmaf(-p.lr, sum, b2[tid]);
     }
     if (tid >= 64 && tid < 64 + W) {
       const int n = tid - 64;
       float sum = 0.0f;
+#pragma unroll 8
       for (int b = 0; b < B; ++b) sum += dl1[b * W + n];
       b1[n] = fmaf(-p.lr, sum, b1[n]);
     }
@@ -285,27 +402,51 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       for (int u = 0; u < MT * 4; ++u)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) dfr[u][nt] = dl1[(4 * u + q4) * W + nt * 16 + n16];
+      auto load_x = [&](int kbi, float (&a)[MT * 4]) {
+        const int kb = min(wave + 4 * kbi, KB - 1);
+#pragma unroll
+        for (int u = 0; u < MT * 4; ++u) a[u] = X[(size_t)(4 * u + q4) * ldx + 16 * kb + n16];
+      };
+      float x_cur[MT * 4], x_nxt[MT * 4];
+      load_x(0, x_cur);
 #pragma unroll
       for (int kbi = 0; kbi < KBI; ++kbi) {
-        const int kb = wave + 4 * kbi;
-        if (kb < KB) {
-          f32x4_t g[NT];
+        if (kbi + 1 < KBI) load_x(kbi + 1, x_nxt);
+        f32x4_t g[NT];
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt) g[nt] = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+        for (int nt = 0; nt < NT; ++nt) g[nt] = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-          for (int u = 0; u < MT * 4; ++u) {
-            const float a = X[(size_t)(4 * u + q4) * ldx + 16 * kb + n16];
+        for (int u = 0; u < MT * 4; ++u)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) g[nt] = mfma16(a, dfr[u][nt], g[nt]);
-          }
+          for (int nt = 0; nt < NT; ++nt) g[nt] = mfma16(x_cur[u], dfr[u][nt], g[nt]);
+        const bool live = wave + 4 * kbi < KB;           // blocks past the end keep zero weights
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) w1[kbi][nt][v] = fmaf(-p.lr, g[nt][v], w1[kbi][nt][v]);
-        }
+          for (int v = 0; v < 4; ++v)
+            w1[kbi][nt][v] = live ? fmaf(-p.lr, g[nt][v], w1[kbi][nt][v]) : 0.0f;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < MT * 4; ++u) x_cur[u] = x_nxt[u];
       }
     }
-    __syncthreads();                                     // X and the small buffers are reused
+    __syncthreads();                                     // X and the small buffers are free
+    // (i) the next minibatch takes its place
+    if (s < my_k) {
+      if constexpr (PF > 0) {
+        gather_store();
+        if (tid < B) { rows[tid] = rows_next[tid]; ylab[tid] = lab_next; }
+      } else {
+        if (tid < B) {
+          const int r = sample_row(p.seed, (uint32_t)i, p.t0 + (uint64_t)s + 1, (uint32_t)tid, p.log2n);
+          rows[tid] = r;
+          ylab[tid] = lab[r];
+        }
+        __syncthreads();
+        gather_direct();
+      }
+      __syncthreads();
+    }
   }
 
   if (aborted) return;
@@ -337,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
 size_t fused2_lds_bytes(const Fused2Plan& pl) {
   const size_t MR = (size_t)pl.MT * 16, W = (size_t)pl.NT * 16;
   const size_t floats = MR * pl.ldx + 4 * MR * W + 2 * MR * W + MR * pl.d2p + W * pl.d2p + W + pl.d2p +
-                        2 * MR + 4;
+                        3 * MR + 4;
   return floats * sizeof(float);
 }
 
@@ -349,6 +490,7 @@ static const void* fused2_pick(int kbi, int nt, int mt) {
 #define PICK(K, N, M) if (kbi == K && nt == N && mt == M) return fused2_symbol<K, N, M>();
   PICK(4, 1, 1) PICK(4, 1, 2) PICK(4, 1, 4) PICK(4, 2, 1) PICK(4, 2, 2) PICK(4, 2, 4)
   PICK(8, 1, 1) PICK(8, 1, 2) PICK(8, 1, 4) PICK(8, 2, 1) PICK(8, 2, 2) PICK(8, 2, 4)
+  PICK(13, 1, 1) PICK(13, 1, 2) PICK(13, 1, 4) PICK(13, 2, 1) PICK(13, 2, 2) PICK(13, 2, 4)
   PICK(16, 1, 1) PICK(16, 1, 2) PICK(16, 1, 4) PICK(16, 2, 1) PICK(16, 2, 2) PICK(16, 2, 4)
 #undef PICK
   return nullptr;
@@ -360,7 +502,7 @@ bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* p
   if (d0 < 4 || (d0 & 3) != 0 || d0 > 1024 || (d1 & 15) != 0 || d2 > 64 || batch > 64) return false;
   pl->MT = batch <= 16 ? 1 : batch <= 32 ? 2 : 4;
   const int kb = (d0 + 15) / 16, kbi_need = (kb + 3) / 4;
-  pl->KBI = kbi_need <= 4 ? 4 : kbi_need <= 8 ? 8 : 16;
+  pl->KBI = kbi_need <= 4 ? 4 : kbi_need <= 8 ? 8 : kbi_need <= 13 ? 13 : 16;
   pl->d2p = (d2 + 15) / 16 * 16;
   int ldx = (d0 + 15) / 16 * 16 + 4;                        // (ldx / 4) odd: conflict-free 16-byte rows
   if (((ldx / 4) & 1) == 0) ldx += 4;
