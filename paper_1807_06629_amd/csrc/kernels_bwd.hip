@@ -1,0 +1,315 @@
+// One pass over a layer's weights for the whole backward step of the per-worker MLP gradient
+//   G_i^t = grad F_i(x_i^{t-1}; zeta_i^t)   and the local update   x_i <- x_i - gamma G_i   (eq. 3)
+// with bfloat16 matrix operands:
+//   dW_l     = H_{l-1}^T D_l,   db_l = colsum(D_l)
+//   W_l     <- W_l - gamma dW_l,   b_l <- b_l - gamma db_l        (fp32 master + bf16 shadow)
+//   D_{l-1}  = (D_l bf16(W_l)^T) * phi'(H_{l-1})                  (with the weights before the update)
+// Every replica has private weights and only B <= 128 batch rows, so the step is bound by moving
+// W_l through HBM.  Computing D_{l-1} from the same fp32 master tile that the update has to read
+// anyway (rounded to bf16 in registers: exactly the shadow's value) removes the separate read of
+// W_l that a stand-alone backward-data product needs.
+//
+// A workgroup (4 wavefronts) owns 64 rows k of W_l of one replica and walks over all columns in
+// tiles of 64.  H_{l-1}[:, k-rows] stays in LDS for the whole walk and the D_{l-1} accumulators
+// (B x 64) stay in registers; per tile it stages D_l[:, n-tile] and bf16(W tile) in LDS, runs both
+// products on the matrix cores (v_mfma_f32_32x32x16_bf16), passes the dW tile through LDS into the
+// row-major layout of the 16-byte weight loads, and writes master and shadow back.  Weight tiles
+// are fetched two tiles ahead, D_l tiles (L2-resident: B x d_l bf16) one tile ahead.
+#include "prsgd_internal.h"
+
+namespace prsgd {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int BMK = 64;            // weight rows (k) per workgroup
+constexpr int BN = 64;             // weight columns (n) per tile
+constexpr int SH = BMK + 16;       // LDS row stride of H^T panel  [b][k]   (bf16 elements)
+constexpr int SD = BN + 16;        // LDS row stride of the D tile [b][n]
+constexpr int SW = BN + 8;         // LDS row stride of the W tile [k][n]
+constexpr int SG = BN + 4;         // LDS row stride of the dW tile [k][n]  (floats)
+#ifndef PRSGD_BWD_STAGES
+#define PRSGD_BWD_STAGES 3
+#endif
+
+// Fragment of an operand whose contraction index is the row index of the LDS tile ([c][row]):
+// LDS transpose load, 4(c) x 16(row) blocks transposed in flight (two loads = 8 contraction
+// elements of the lane's row).
+__device__ __forceinline__ bf16x8_t frag_trans(const uint16_t* lds, int stride, int row_block, int kk,
+                                               int lane) {
+  typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+  typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
+  const int g = lane >> 4, r = lane & 15;
+  const int c = kk * 16 + 8 * (g >> 1) + (r >> 2);
+  const int row = row_block + 16 * (g & 1) + 4 * (r & 3);
+  const uint16_t* p = lds + c * stride + row;
+  const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
+  const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + 4 * stride));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+// Fragment of an operand stored [row][c]: one 16-byte read.
+__device__ __forceinline__ bf16x8_t frag_contig(const uint16_t* lds, int stride, int row_block, int kk,
+                                                int lane) {
+  const u16x8_t u = *reinterpret_cast<const u16x8_t*>(lds + (row_block + (lane & 31)) * stride + kk * 16 +
+                                                      (lane >> 5) * 8);
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+__device__ __forceinline__ f32x16_t mfma_bf16(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float dact_from_h(float h, int act) {
+  return act == PRSGD_TANH ? (1.0f - h * h) : (h > 0.0f ? 1.0f : 0.0f);
+}
+
+// MB: 32-row tiles of the minibatch held on chip (B <= 32 MB).  DX: also produce D_{l-1}.
+// S: weight tiles in flight per workgroup (register sets).
+template <int MB, bool DX, int S>
+__global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
+  constexpr int BR = 32 * MB;
+  constexpr int NTD = DX ? (2 * MB + 3) / 4 : 1;     // D_{l-1} accumulator tiles per wavefront
+
+  // workgroup -> (replica, k-tile); all tiles of a replica on one XCD when N is a multiple of 8
+  const int tiles = (p.K + BMK - 1) / BMK;
+  int g, tile;
+  if ((p.n_groups & 7) == 0) {
+    const int slot = blockIdx.x >> 3;
+    g = (blockIdx.x & 7) + 8 * (slot / tiles);
+    tile = slot % tiles;
+  } else {
+    g = blockIdx.x / tiles;
+    tile = blockIdx.x % tiles;
+  }
+  if (p.worker_steps != nullptr && p.step >= p.worker_steps[g]) return;
+  const int k0 = tile * BMK;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* HT = reinterpret_cast<uint16_t*>(smem);            // [BR][SH]
+  uint16_t* Dl = HT + BR * SH;                                 // [BR][SD]
+  uint16_t* Wl = Dl + BR * SD;                                 // [BMK][SW]
+  float* Gl = reinterpret_cast<float*>(Wl + BMK * SW);         // [BMK][SG]
+  float* Bs = Gl + BMK * SG;                                   // [4][BN] partial column sums
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr32 = lane & 31, kb = lane >> 5;
+
+  const uint16_t* h_g = p.h + (size_t)g * p.h_gs;
+  const uint16_t* d_g = p.d + (size_t)g * p.d_gs;
+  float* w_g = p.params + (size_t)g * p.p_gs + p.w_off;
+  uint16_t* s_g = p.shadow + (size_t)g * p.p_gs + p.w_off;
+  const bool nt = p.streaming != 0;
+
+  // ---- staging helpers ---------------------------------------------------------------------
+  // B x 64 bf16 panel (H^T columns or a D tile): MB 16-byte vectors per thread, row = q*32 + tid/8
+  auto fetch_panel = [&](uint4 (&reg)[MB], const uint16_t* src, int ld, int col0, int n_cols) -> uint32_t {
+    uint32_t mask = 0;
+#pragma unroll
+    for (int q = 0; q < MB; ++q) {
+      const int row = q * 32 + (tid >> 3), col = col0 + (tid & 7) * 8;
+      const bool ok = row < p.B && col < n_cols;
+      reg[q] = *reinterpret_cast<const uint4*>(src + (ok ? (size_t)row * ld + col : (size_t)0));
+      mask |= (ok ? 1u : 0u) << q;
+    }
+    return mask;
+  };
+  auto stash_panel = [&](uint16_t* lds, int stride, const uint4 (&reg)[MB], uint32_t mask) {
+#pragma unroll
+    for (int q = 0; q < MB; ++q) {
+      const uint32_t keep = 0u - ((mask >> q) & 1u);
+      const uint4 v = make_uint4(reg[q].x & keep, reg[q].y & keep, reg[q].z & keep, reg[q].w & keep);
+      *reinterpret_cast<uint4*>(lds + (q * 32 + (tid >> 3)) * stride + (tid & 7) * 8) = v;
+    }
+  };
+  // 64 x 64 fp32 weight tile: 4 16-byte vectors per thread, row = q*16 + tid/16, column 4*(tid%16)
+  auto fetch_w = [&](f32x4_t (&reg)[4], int n0) -> uint32_t {
+    uint32_t mask = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int k = k0 + q * 16 + (tid >> 4), n = n0 + 4 * (tid & 15);
+      const bool ok = k < p.K && n < p.Nn;
+      const f32x4_t* src = reinterpret_cast<const f32x4_t*>(w_g + (ok ? (size_t)k * p.ldw + n : (size_t)0));
+      reg[q] = nt ? __builtin_nontemporal_load(src) : *src;
+      mask |= (ok ? 1u : 0u) << q;
+    }
+    return mask;
+  };
+  auto stash_w = [&](const f32x4_t (&reg)[4], uint32_t mask) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bool ok = (mask >> q) & 1u;
+      uint2 hv;
+      hv.x = ok ? ((uint32_t)f32_to_bf16_rne(reg[q].x) | ((uint32_t)f32_to_bf16_rne(reg[q].y) << 16)) : 0u;
+      hv.y = ok ? ((uint32_t)f32_to_bf16_rne(reg[q].z) | ((uint32_t)f32_to_bf16_rne(reg[q].w) << 16)) : 0u;
+      *reinterpret_cast<uint2*>(Wl + (q * 16 + (tid >> 4)) * SW + 4 * (tid & 15)) = hv;
+    }
+  };
+
+  // ---- prologue -----------------------------------------------------------------------------
+  const int n_t = (p.Nn + BN - 1) / BN;
+  uint4 pr[MB];
+  f32x4_t wr[S][4];
+  uint32_t wm[S], dm;
+  {
+    const uint32_t hm = fetch_panel(pr, h_g, p.ldh, k0, p.K);
+    wm[0] = fetch_w(wr[0], 0);
+    stash_panel(HT, SH, pr, hm);
+  }
+  dm = fetch_panel(pr, d_g, p.ldd, 0, p.Nn);
+#pragma unroll
+  for (int st = 1; st < S; ++st) {
+    wm[st] = 0;
+    if (st < n_t) wm[st] = fetch_w(wr[st], st * BN);
+  }
+
+  f32x16_t acc_dx[NTD];
+#pragma unroll
+  for (int t = 0; t < NTD; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc_dx[t][v] = 0.0f;
+
+  const int wk = wave >> 1, wn = wave & 1;             // this wavefront's 32x32 block of the dW tile
+  // db_l: the k-tile workgroups of a replica take the column tiles in turn, so that no
+  // workgroup carries all of the bias work (the launch ends with its slowest workgroup)
+
+  // one tile: (wr, wm) holds the weights of tile `it` and is refilled with tile it+S
+  auto tile_step = [&](int it, f32x4_t (&wr)[4], uint32_t& wm) {
+    const int n0 = it * BN;
+    stash_panel(Dl, SD, pr, dm);
+    if (DX) stash_w(wr, wm);
+    __syncthreads();
+    if (it + 1 < n_t) dm = fetch_panel(pr, d_g, p.ldd, n0 + BN, p.Nn);
+
+    // dW tile block (wk, wn): contraction over the minibatch
+    f32x16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < BR / 16; ++kk)
+      acc = mfma_bf16(frag_trans(HT, SH, wk * 32, kk, lane), frag_trans(Dl, SD, wn * 32, kk, lane), acc);
+    // D_{l-1} blocks: contraction over this tile's columns, with the pre-update weights
+    if (DX) {
+#pragma unroll
+      for (int t = 0; t < NTD; ++t) {
+        const int blk = wave + 4 * t;
+        if (blk < 2 * MB) {
+          const int mb = blk >> 1, kblk = blk & 1;
+#pragma unroll
+          for (int kk = 0; kk < BN / 16; ++kk)
+            acc_dx[t] = mfma_bf16(frag_contig(Dl, SD, mb * 32, kk, lane),
+                                  frag_contig(Wl, SW, kblk * 32, kk, lane), acc_dx[t]);
+        }
+      }
+    }
+    // db: column sums of the (rounded) delta tile; rows beyond B are zero.  Each wavefront sums
+    // a quarter of the rows, the four partial sums are added in order after the barrier.
+    const bool bias_turn = (it % tiles) == tile;
+    if (bias_turn) {
+      float cs = 0.0f;
+#pragma unroll 8
+      for (int b = wave * (BR / 4); b < (wave + 1) * (BR / 4); ++b) cs += bf16_to_f32(Dl[b * SD + lane]);
+      Bs[wave * BN + lane] = cs;
+    }
+    // accumulator element v of lane (lr32, kb) is C[8 (v/4) + 4 kb + v%4][lr32]
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      Gl[(wk * 32 + 8 * (v / 4) + 4 * kb + (v % 4)) * SG + wn * 32 + lr32] = acc[v];
+    __syncthreads();
+
+    // eq. (3) on the tile, in the layout of the weight loads
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if ((wm >> q) & 1u) {
+        const int row = q * 16 + (tid >> 4), c = 4 * (tid & 15);
+        const f32x4_t gr = *reinterpret_cast<const f32x4_t*>(Gl + row * SG + c);
+        f32x4_t w = wr[q];
+        w.x = fmaf(-p.lr, gr.x, w.x);
+        w.y = fmaf(-p.lr, gr.y, w.y);
+        w.z = fmaf(-p.lr, gr.z, w.z);
+        w.w = fmaf(-p.lr, gr.w, w.w);
+        uint2 hv;
+        hv.x = (uint32_t)f32_to_bf16_rne(w.x) | ((uint32_t)f32_to_bf16_rne(w.y) << 16);
+        hv.y = (uint32_t)f32_to_bf16_rne(w.z) | ((uint32_t)f32_to_bf16_rne(w.w) << 16);
+        const size_t off = (size_t)(k0 + row) * p.ldw + n0 + c;
+        typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+        const u32x2_t hv2 = {hv.x, hv.y};
+        if (nt) {
+          __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(w_g + off));
+          __builtin_nontemporal_store(hv2, reinterpret_cast<u32x2_t*>(s_g + off));
+        } else {
+          *reinterpret_cast<f32x4_t*>(w_g + off) = w;
+          *reinterpret_cast<u32x2_t*>(s_g + off) = hv2;
+        }
+      }
+    }
+    if (bias_turn && tid < BN && n0 + tid < p.Nn) {
+      const float cs = ((Bs[tid] + Bs[BN + tid]) + Bs[2 * BN + tid]) + Bs[3 * BN + tid];
+      float* bptr = p.params + (size_t)g * p.p_gs + p.b_off + n0 + tid;
+      *bptr = fmaf(-p.lr, cs, *bptr);
+    }
+    if (it + S < n_t) wm = fetch_w(wr, n0 + S * BN);
+  };
+
+  for (int base = 0; base < n_t; base += S) {
+#pragma unroll
+    for (int st = 0; st < S; ++st)
+      if (base + st < n_t) tile_step(base + st, wr[st], wm[st]);
+  }
+
+  // ---- D_{l-1} = acc * phi'(H_{l-1}) -------------------------------------------------------
+  if (DX) {
+    uint16_t* dx_g = p.dx + (size_t)g * p.dx_gs;
+#pragma unroll
+    for (int t = 0; t < NTD; ++t) {
+      const int blk = wave + 4 * t;
+      if (blk < 2 * MB) {
+        const int mb = blk >> 1, kblk = blk & 1;
+        const int k = k0 + kblk * 32 + lr32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int b = mb * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
+          if (b < p.B && k < p.K) {
+            const float hval = bf16_to_f32(HT[b * SH + kblk * 32 + lr32]);
+            dx_g[(size_t)b * p.lddx + k] = f32_to_bf16_rne(acc_dx[t][v] * dact_from_h(hval, p.act));
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int MB, bool DX>
+hipError_t launch_bwd_one(const BwdArgs& p, hipStream_t s) {
+  constexpr int S = PRSGD_BWD_STAGES;
+  constexpr int BR = 32 * MB;
+  constexpr size_t kLds =
+      sizeof(uint16_t) * (BR * SH + BR * SD + BMK * SW) + sizeof(float) * (BMK * SG + 4 * BN);
+  auto kernel = grouped_bwd_kernel<MB, DX, S>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles = (p.K + BMK - 1) / BMK;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles * p.n_groups)), dim3(kThreads), kLds, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool bwd_fused_supported(int batch) { return batch >= 1 && batch <= 128; }
+
+hipError_t launch_bwd_fused(const BwdArgs& p, hipStream_t s) {
+  if (p.K <= 0 || p.Nn <= 0 || p.n_groups <= 0) return hipSuccess;
+  if (!bwd_fused_supported(p.B)) return hipErrorInvalidValue;
+  const bool dx = p.dx != nullptr;
+  if (p.B <= 32) return dx ? launch_bwd_one<1, true>(p, s) : launch_bwd_one<1, false>(p, s);
+  if (p.B <= 64) return dx ? launch_bwd_one<2, true>(p, s) : launch_bwd_one<2, false>(p, s);
+  return dx ? launch_bwd_one<4, true>(p, s) : launch_bwd_one<4, false>(p, s);
+}
+
+}  // namespace prsgd

@@ -12,6 +12,8 @@
 // (v_mfma_f32_32x32x16_bf16 or v_mfma_f32_32x32x2_f32).  Operand tiles are staged through LDS in
 // their natural memory orientation with 16-byte global loads; an operand whose contraction
 // index is the strided one is transposed while its MFMA fragments are read out of LDS.
+#include <type_traits>
+
 #include "prsgd_internal.h"
 
 namespace prsgd {
@@ -251,32 +253,34 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   const bool bias_wg = kIsDw && m0 == 0;
   float colsum = 0.0f;                       // db: thread n sums column n of the delta tile
 
-  // Software pipeline: two LDS stages, and two register sets so that the global loads of
-  // tiles it+1 and it+2 are both in flight while tile `it` is multiplied -- one tile of compute
-  // is shorter than the HBM latency it has to hide.
-  const int n_k = (p.Kc + BK - 1) / BK;
-  uint4 a_r0[IOA::NPT], b_r0[IOB::NPT], a_r1[IOA::NPT], b_r1[IOB::NPT];
-  uint32_t a_m0, b_m0, a_m1 = 0, b_m1 = 0;         // validity masks of the register sets
-  a_m0 = IOA::fetch(a_r0, a_src, p.lda, m0, p.M, 0, p.Kc, tid);
-  b_m0 = IOB::fetch(b_r0, b_src, p.ldb, n0, p.N, 0, p.Kc, tid);
-  IOA::stash(a_lds0, a_r0, a_m0, tid);
-  IOB::stash(b_lds0, b_r0, b_m0, tid);
-  // The weight-gradient product contracts over the minibatch only (one or two tiles): it keeps
-  // the plain one-tile prefetch and spends its registers on the streamed weights instead.
+  // Software pipeline: two LDS stages and R register sets, so that the global loads of tiles
+  // it+2 .. it+1+R are all in flight while tile `it` is multiplied -- one tile of compute is far
+  // shorter than the HBM latency it has to hide, and a launch has few workgroups per compute unit.
+  // Tile j (j >= 1) travels through register set j % R.  The weight-gradient product contracts
+  // over the minibatch only (one or two tiles): it keeps a single LDS stage and a one-tile
+  // prefetch and spends its registers on the streamed weights instead.
   constexpr bool kDeep = !kIsDw;
-  if (kDeep && n_k > 1) {
-    a_m0 = IOA::fetch(a_r0, a_src, p.lda, m0, p.M, BK, p.Kc, tid);
-    b_m0 = IOB::fetch(b_r0, b_src, p.ldb, n0, p.N, BK, p.Kc, tid);
-  }
-  if (kDeep && n_k > 2) {
-    a_m1 = IOA::fetch(a_r1, a_src, p.lda, m0, p.M, 2 * BK, p.Kc, tid);
-    b_m1 = IOB::fetch(b_r1, b_src, p.ldb, n0, p.N, 2 * BK, p.Kc, tid);
+  constexpr int R = kDeep ? 4 : 1;
+  const int n_k = (p.Kc + BK - 1) / BK;
+  uint4 a_r[R][IOA::NPT], b_r[R][IOB::NPT];
+  uint32_t a_m[R], b_m[R];                           // validity masks of the register sets
+#pragma unroll
+  for (int r = 0; r < R; ++r) { a_m[r] = 0; b_m[r] = 0; }
+  a_m[0] = IOA::fetch(a_r[0], a_src, p.lda, m0, p.M, 0, p.Kc, tid);
+  b_m[0] = IOB::fetch(b_r[0], b_src, p.ldb, n0, p.N, 0, p.Kc, tid);
+  IOA::stash(a_lds0, a_r[0], a_m[0], tid);
+  IOB::stash(b_lds0, b_r[0], b_m[0], tid);
+  if constexpr (kDeep) {
+#pragma unroll
+    for (int j = 1; j <= R; ++j) {
+      if (j < n_k) {
+        a_m[j % R] = IOA::fetch(a_r[j % R], a_src, p.lda, m0, p.M, j * BK, p.Kc, tid);
+        b_m[j % R] = IOB::fetch(b_r[j % R], b_src, p.ldb, n0, p.N, j * BK, p.Kc, tid);
+      }
+    }
   }
   __syncthreads();
 
-  // One pipeline step on tile `it`; (ra, rb) is the register set that holds tile it+1 and is
-  // refilled with tile it+3.  STEADY = all of tiles it+1 .. it+3 exist, so the step is
-  // straight-line code and the loads of the other register set can stay in flight across it.
   auto compute = [&](int cur) {
     const E* a_cur = a_lds0 + cur * A_ELEMS;
     const E* b_cur = b_lds0 + cur * B_ELEMS;
@@ -306,50 +310,53 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
       for (int c = 0; c < BK; ++c) colsum += from_elem<T>(b_cur[c * IOB::STRIDE + tid]);
     }
   };
-  auto steady_step = [&](int it, uint4 (&ra)[IOA::NPT], uint4 (&rb)[IOB::NPT], uint32_t& ma, uint32_t& mb) {
-    const int cur = it & 1;
-    compute(cur);
-    IOA::stash(a_lds0 + (cur ^ 1) * A_ELEMS, ra, ma, tid);
-    IOB::stash(b_lds0 + (cur ^ 1) * B_ELEMS, rb, mb, tid);
-    ma = IOA::fetch(ra, a_src, p.lda, m0, p.M, (it + 3) * BK, p.Kc, tid);
-    mb = IOB::fetch(rb, b_src, p.ldb, n0, p.N, (it + 3) * BK, p.Kc, tid);
-    __syncthreads();
-  };
-  auto step = [&](int it, uint4 (&ra)[IOA::NPT], uint4 (&rb)[IOB::NPT], uint32_t& ma, uint32_t& mb) {
-    const int cur = it & 1;
-    compute(cur);
-    if (it + 1 < n_k) {
-      IOA::stash(a_lds0 + (cur ^ 1) * A_ELEMS, ra, ma, tid);
-      IOB::stash(b_lds0 + (cur ^ 1) * B_ELEMS, rb, mb, tid);
-    }
-    if (it + 3 < n_k) {
-      ma = IOA::fetch(ra, a_src, p.lda, m0, p.M, (it + 3) * BK, p.Kc, tid);
-      mb = IOB::fetch(rb, b_src, p.ldb, n0, p.N, (it + 3) * BK, p.Kc, tid);
-    }
-    __syncthreads();
-  };
   if constexpr (kDeep) {
+    // One pipeline step on tile `it` (it % R == U): multiply the LDS stage it & 1, move tile
+    // it+1 from its register set to the other stage, refill that set with tile it+1+R.
+    // STEADY = all of these tiles exist: straight-line code, so the loads of the other register
+    // sets can stay in flight across the step.
+    auto step = [&](int it, auto u_tag, auto steady_tag) {
+      constexpr int U = decltype(u_tag)::value;
+      constexpr bool STEADY = decltype(steady_tag)::value;
+      constexpr int SET = (U + 1) % R, CUR = U & 1;
+      compute(CUR);
+      if (STEADY || it + 1 < n_k) {
+        IOA::stash(a_lds0 + (CUR ^ 1) * A_ELEMS, a_r[SET], a_m[SET], tid);
+        IOB::stash(b_lds0 + (CUR ^ 1) * B_ELEMS, b_r[SET], b_m[SET], tid);
+      }
+      if (STEADY || it + 1 + R < n_k) {
+        a_m[SET] = IOA::fetch(a_r[SET], a_src, p.lda, m0, p.M, (it + 1 + R) * BK, p.Kc, tid);
+        b_m[SET] = IOB::fetch(b_r[SET], b_src, p.ldb, n0, p.N, (it + 1 + R) * BK, p.Kc, tid);
+      }
+      __syncthreads();
+    };
+    static_assert(R == 4, "the unrolled pipeline below is written for four register sets");
+    using std::integral_constant;
     int it = 0;
-    for (; it + 4 < n_k; it += 2) {            // tiles it+3 and it+4 exist: no conditionals inside
-      steady_step(it, a_r0, b_r0, a_m0, b_m0);
-      steady_step(it + 1, a_r1, b_r1, a_m1, b_m1);
+    for (; it + 2 * R < n_k; it += R) {        // tiles up to it+3+1+R exist: no conditionals inside
+      step(it, integral_constant<int, 0>{}, integral_constant<bool, true>{});
+      step(it + 1, integral_constant<int, 1>{}, integral_constant<bool, true>{});
+      step(it + 2, integral_constant<int, 2>{}, integral_constant<bool, true>{});
+      step(it + 3, integral_constant<int, 3>{}, integral_constant<bool, true>{});
     }
-    for (; it < n_k; it += 2) {                // drain (it stays even, so the sets keep their roles)
-      step(it, a_r0, b_r0, a_m0, b_m0);
-      if (it + 1 < n_k) step(it + 1, a_r1, b_r1, a_m1, b_m1);
+    for (; it < n_k; it += R) {                // drain (it stays a multiple of R)
+      step(it, integral_constant<int, 0>{}, integral_constant<bool, false>{});
+      if (it + 1 < n_k) step(it + 1, integral_constant<int, 1>{}, integral_constant<bool, false>{});
+      if (it + 2 < n_k) step(it + 2, integral_constant<int, 2>{}, integral_constant<bool, false>{});
+      if (it + 3 < n_k) step(it + 3, integral_constant<int, 3>{}, integral_constant<bool, false>{});
     }
   } else {
     for (int it = 0; it < n_k; ++it) {         // single LDS stage, next tile prefetched in registers
       const bool more = it + 1 < n_k;
       if (more) {
-        a_m0 = IOA::fetch(a_r0, a_src, p.lda, m0, p.M, (it + 1) * BK, p.Kc, tid);
-        b_m0 = IOB::fetch(b_r0, b_src, p.ldb, n0, p.N, (it + 1) * BK, p.Kc, tid);
+        a_m[0] = IOA::fetch(a_r[0], a_src, p.lda, m0, p.M, (it + 1) * BK, p.Kc, tid);
+        b_m[0] = IOB::fetch(b_r[0], b_src, p.ldb, n0, p.N, (it + 1) * BK, p.Kc, tid);
       }
       compute(0);
       if (more) {
         __syncthreads();
-        IOA::stash(a_lds0, a_r0, a_m0, tid);
-        IOB::stash(b_lds0, b_r0, b_m0, tid);
+        IOA::stash(a_lds0, a_r[0], a_m[0], tid);
+        IOB::stash(b_lds0, b_r[0], b_m[0], tid);
         __syncthreads();
       }
     }

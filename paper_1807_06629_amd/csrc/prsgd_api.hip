@@ -17,7 +17,7 @@ namespace prsgd {
 const char* kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
                                         "sgd_update", "average", "mean",       "broadcast", "lsq_steps",
-                                        "mlp2_epoch"};
+                                        "mlp2_epoch", "gemm_bwd"};
   return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
 }
 }  // namespace prsgd
@@ -255,8 +255,25 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
                              ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.row_loss), N, B, lo.d[L],
                              lo.ld[L], bf16, worker_steps, step, s));
 
-  // backward: D_{l-1} needs the pre-update W_l, so it runs before layer l's weight kernel
-  for (int l = L; l >= 1; --l) {
+  // backward.  bf16 operands with the fused update: one kernel per layer does the weight
+  // gradient, eq. (3) and the delta of the layer below in a single pass over W_l.
+  const bool fused_bwd = bf16 && c.fused_update && bwd_fused_supported(B);
+  for (int l = L; fused_bwd && l >= 1; --l) {
+    BwdArgs q;
+    memset(&q, 0, sizeof(q));
+    q.h = reinterpret_cast<const uint16_t*>(act_in(l - 1)); q.h_gs = (long)B * lo.ld[l - 1]; q.ldh = lo.ld[l - 1];
+    q.d = ctx->at<uint16_t>(cv.delta[l]); q.d_gs = (long)B * lo.ld[l]; q.ldd = lo.ld[l];
+    q.params = ctx->params; q.shadow = ctx->shadow(); q.p_gs = lo.m_pad;
+    q.w_off = lo.w_off[l - 1]; q.b_off = lo.b_off[l - 1]; q.ldw = lo.ld[l];
+    if (l > 1) { q.dx = ctx->at<uint16_t>(cv.delta[l - 1]); q.dx_gs = (long)B * lo.ld[l - 1]; q.lddx = lo.ld[l - 1]; }
+    q.B = B; q.K = lo.d[l - 1]; q.Nn = lo.d[l];
+    q.n_groups = N; q.act = c.activation; q.streaming = ctx->streaming ? 1 : 0;
+    q.lr = ctx->lr;
+    q.worker_steps = worker_steps; q.step = step;
+    LAUNCH(ctx, KK_BWD, launch_bwd_fused(q, s));
+  }
+  // otherwise: D_{l-1} needs the pre-update W_l, so it runs before layer l's weight kernel
+  for (int l = L; !fused_bwd && l >= 1; --l) {
     if (l > 1) {
       GemmArgs p = base;
       p.a = ctx->at<void>(cv.delta[l]); p.a_gs = (long)B * lo.ld[l]; p.lda = lo.ld[l];

@@ -60,8 +60,24 @@ struct GemmArgs {
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
-  KK_LSQ, KK_FUSED2, KK_COUNT
+  KK_LSQ, KK_FUSED2, KK_BWD, KK_COUNT
 };
+
+// Fused backward step of one layer with bf16 operands (kernels_bwd.hip): weight gradient, local
+// update of W_l and b_l, and the delta of the layer below, in one pass over W_l.
+struct BwdArgs {
+  const uint16_t* h; long h_gs; int ldh;        // H_{l-1} [N][B][ldh]
+  const uint16_t* d; long d_gs; int ldd;        // D_l     [N][B][ldd]
+  float* params; uint16_t* shadow; long p_gs;   // fp32 master and bf16 shadow, replica stride
+  long w_off, b_off; int ldw;
+  uint16_t* dx; long dx_gs; int lddx;           // D_{l-1} [N][B][lddx]; nullptr for the first layer
+  int B, K, Nn;                                 // minibatch rows, d_{l-1}, d_l
+  int n_groups, act, streaming;
+  float lr;
+  const int* worker_steps; int step;            // Algorithm 3 mask (nullptr = all active)
+};
+bool bwd_fused_supported(int batch);
+hipError_t launch_bwd_fused(const BwdArgs& p, hipStream_t s);
 
 // Epoch kernel for fp32 MLPs with one hidden layer (kernels_fused2.hip).
 struct Fused2Plan {
