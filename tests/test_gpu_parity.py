@@ -265,6 +265,83 @@ def test_c3_shape_noniid_reduced(P, D):
     P.prsgd_destroy(h)
 
 
+def test_bf16_fused_backward_kernel_runs_and_falls_back_above_128_rows(P, D):
+    # B <= 128: one fused backward kernel per layer; B > 128: the separate products
+    for batch, expect in ((48, "gemm_bwd"), (160, "gemm_dw")):
+        w = small_mlp(dims=(72, 136, 40, 10), batch=batch, n_workers=2, gemm_dtype="bf16",
+                      activation="relu", rows_per_worker=256, interval=3, iterations=6)
+        inp = inputs_for(w)
+        h = _open(D, w, inp)
+        names = _kernel_names(P, h, w.iterations, w.interval)
+        assert expect in names, names
+        assert ("gemm_dx" in names) == (expect == "gemm_dw")
+        want = oracle_run(w, inp)
+        assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=BF16_LOSS_TOL)
+        assert rel_err(D.read_all(h), want["x"]) <= 5e-3
+        P.prsgd_destroy(h)
+
+
+def test_bf16_heterogeneous_steps_mask_the_fused_backward_kernel(P, D):
+    w = small_mlp(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="tanh")
+    inp = inputs_for(w)
+    steps = [4, 0, 2, 1]
+    h = _open(D, w, inp)
+    D.run_algorithm3(h, steps, 2)
+    args = oracle_args(w, inp)
+    want = oracle.run_heterogeneous(**args, lr=w.lr, worker_steps=steps, n_epochs=2)
+    assert P.prsgd_iteration(h) == want["t"]
+    assert rel_err(D.read_all(h), want["x"]) <= 5e-3
+    P.prsgd_destroy(h)
+
+
+# --------------------------------------------------------------------------- full-size shapes, as benchmarked
+def test_c2_full_horizon(P, D):
+    # the benchmark's default workload at its full T = 2000, I = 16 (epoch kernel, 125 restarts)
+    w = get_workload("c2")
+    inp = make_inputs(w)
+    h = _open(D, w, inp)
+    P.prsgd_run(h, w.iterations, w.interval)
+    want = oracle_run(w, inp)
+    got = D.read_all(h)
+    assert rel_err(got, want["x"]) <= T_STEP_TOL
+    assert np.array_equal(got[0], got[-1])              # I | T: the run ends on a restart
+    assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=5e-2, atol=1e-5)
+    P.prsgd_destroy(h)
+
+
+@pytest.mark.parametrize("interval", [1, 8])
+def test_c4_full_shape_long_run(P, D, interval):
+    w = get_workload("c4").scaled(iterations=1000, rows_per_worker=1024)
+    inp = make_inputs(w)
+    h = _open(D, w, inp)
+    P.prsgd_run(h, w.iterations, interval)
+    want = oracle_run(w, inp, interval=interval)
+    assert rel_err(D.read_all(h), want["x"]) <= T_STEP_TOL
+    P.prsgd_destroy(h)
+
+
+@pytest.mark.parametrize("name,iters,interval", [("c3", 4, 2), ("c5", 2, 2)])
+def test_bf16_full_size_replicas(P, D, name, iters, interval):
+    # full layer sizes, worker count and batch (the launch shapes the benchmark times); a short
+    # horizon and a smaller shard keep the fp64 oracle to seconds
+    w = get_workload(name).scaled(rows_per_worker=512, iterations=iters, interval=interval)
+    inp = make_inputs(w)
+    h = _open(D, w, inp)
+    log = []
+    want = oracle_run(w, inp, record=log.append)
+    for rec in log:
+        P.prsgd_run(h, 1, w.interval)
+        got = P.prsgd_read_loss(h)
+        assert np.allclose(got, rec["losses"], rtol=BF16_LOSS_TOL, atol=BF16_LOSS_TOL * 0.02), \
+            (rec["t"], got, rec["losses"])
+    # sampled replicas, every parameter
+    for i in (0, w.n_workers - 1):
+        assert rel_err(P.prsgd_read_params(h, i), want["x"][i]) <= 5e-3
+    xbar = P.prsgd_read_params(h, -1)
+    assert rel_err(xbar, oracle.node_average(want["x"])) <= 5e-3
+    P.prsgd_destroy(h)
+
+
 # --------------------------------------------------------------------------- restart average
 @pytest.mark.parametrize("n_workers", [1, 2, 3, 8, 19, 64])
 def test_restart_average_properties(P, D, n_workers):
