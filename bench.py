@@ -157,6 +157,8 @@ def main() -> int:
     ap.add_argument("--interval", type=int, default=None)
     ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hbm-average", action="store_true",
+                    help="skip the extra HBM-scale timing of the averaging kernel")
     ap.add_argument("--rows", type=int, default=None, help="rows per worker (default: workload's)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="time the plain copy kernel (known traffic) instead of a workload")
@@ -286,7 +288,7 @@ def main() -> int:
     prsgd.prsgd_destroy(h)
     del h
     torch.cuda.empty_cache()
-    if restart is not None and restart["bytes"] < (1 << 29):
+    if restart is not None and restart["bytes"] < (1 << 29) and not args.no_hbm_average:
         # this workload's replicas are cache-resident: also report the kernel at HBM scale
         out["restart_average_hbm"] = restart_average_at_hbm_scale(prsgd, drivers, get_workload,
                                                                   make_inputs)
