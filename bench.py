@@ -31,7 +31,8 @@ KERNEL_SYMBOL = {
     "gemm_dx": "grouped_gemm_kernel<.., OP_CONTIG, OP_CONTIG>",
     "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>", "gemm_bwd": "grouped_bwd_kernel",
     "softmax_xent": "softmax_xent_kernel",
-    "sgd_update": "update_kernel", "average": "average_kernel", "lsq_steps": "lsq_steps_kernel",
+    "sgd_update": "update_kernel", "average": "average_kernel", "restart_mean": "mean_kernel",
+    "lsq_steps": "lsq_steps_kernel",
     "mlp2_epoch": "mlp2_epoch_kernel",
 }
 
@@ -45,6 +46,7 @@ def algorithmic_work(w):
         d = w.dims[0]
         out["lsq_steps"] = {"bytes": n * b * (d + 1) * 4, "flops": 4 * n * b * d}
         out["average"] = {"bytes": 8 * n * d, "flops": n * d}
+        out["restart_mean"] = {"bytes": 4 * n * d + 4 * d, "flops": n * d}
         return out
     es = 2 if w.gemm_dtype == "bf16" else 4          # operand element size
     dims = w.dims
@@ -74,6 +76,9 @@ def algorithmic_work(w):
     out["mlp2_epoch"] = {"bytes": n * b * (dims[0] + 1) * 4 + 8.0 * n * m / max(1, w.interval),
                          "flops": fwd_f + dx_f + dw_f}
     out["average"] = {"bytes": n * m * 8 + n * pw * shadow, "flops": n * m}
+    # restart with the broadcast deferred: every replica read once, the node average (and its
+    # bf16 image) written once
+    out["restart_mean"] = {"bytes": n * m * 4 + m * 4 + pw * shadow, "flops": n * m}
     return out
 
 
@@ -128,24 +133,59 @@ def cpu_baseline(w, inp, budget_s=20.0):
 
 
 def restart_average_at_hbm_scale(prsgd, drivers, get_workload, make_inputs, reps=20):
-    """The averaging kernel (eq. 2) timed on a replica set far larger than the caches: the
-    largest workload's replicas ([8][54.4M] fp32 + bf16 shadow, 4.36 GB per pass) with a token
-    data shard.  HIP events on the library's stream, through the library's own profiling."""
+    """The restart kernels (eq. 2) timed on a replica set far larger than the caches: the
+    largest workload's replicas ([8][54.4M] fp32 + bf16 shadow) with a token data shard.
+    `average` = read every replica, overwrite every replica (4.36 GB per pass); `restart_mean` =
+    the deferred-broadcast form, every replica read, the average written once (2.07 GB).  HIP
+    events on the library's stream, through the library's own profiling."""
     w = get_workload("c5").scaled(rows_per_worker=64, batch=8)
     h = drivers.open_workload(w, make_inputs(w), device="cuda:0")
-    for _ in range(3):
-        prsgd.prsgd_average(h)
-    prsgd.prsgd_profile_enable(h, True)
-    for _ in range(reps):
-        prsgd.prsgd_average(h)
-    stats = {s["name"]: s for s in prsgd.prsgd_profile_read(h)}
-    prsgd.prsgd_profile_enable(h, False)
+    out = {"workload": "replica set of c5: N=8, m=54440936, fp32 master + bf16 shadow"}
+    for lazy, label in ((False, "average"), (True, "restart_mean")):
+        prsgd.prsgd_set_lazy_restart(h, lazy)
+        def once():
+            prsgd.prsgd_average(h)
+            if lazy:
+                prsgd.prsgd_set_lazy_restart(h, False)   # broadcast (not timed under this label)
+                prsgd.prsgd_set_lazy_restart(h, True)
+        for _ in range(3):
+            once()
+        prsgd.prsgd_profile_enable(h, True)
+        for _ in range(reps):
+            once()
+        stats = {s["name"]: s for s in prsgd.prsgd_profile_read(h)}
+        prsgd.prsgd_profile_enable(h, False)
+        work = algorithmic_work(w)[label]["bytes"]
+        sec = stats[label]["total_ms"] * 1e-3 / stats[label]["launches"]
+        out[label] = {"bytes": work, "avg_us": 1e6 * sec, "GBps": work / sec / 1e9,
+                      "frac_of_hbm_peak": work / sec / 1e9 / HBM_PEAK_GBPS,
+                      "launches_timed": stats[label]["launches"]}
     prsgd.prsgd_destroy(h)
-    work = algorithmic_work(w)["average"]["bytes"]
-    sec = stats["average"]["total_ms"] * 1e-3 / stats["average"]["launches"]
-    return {"workload": "replica set of c5: N=8, m=54440936, fp32 master + bf16 shadow",
-            "bytes": work, "avg_us": 1e6 * sec, "GBps": work / sec / 1e9,
-            "frac_of_hbm_peak": work / sec / 1e9 / HBM_PEAK_GBPS, "launches_timed": reps}
+    return out
+
+
+def standalone_update_at_hbm_scale(prsgd, n_elems=1 << 28, reps=20):
+    """The stand-alone elementwise form of eq. (3), x <- x - gamma g (+ bf16 image of x), on
+    2^28 elements (1 GiB per fp32 vector): 12 B/element of fp32 traffic + 2 B/element shadow."""
+    import torch
+    x = torch.zeros(n_elems, dtype=torch.float32, device="cuda:0")
+    g = torch.ones(n_elems, dtype=torch.float32, device="cuda:0")
+    sh = torch.zeros(n_elems, dtype=torch.bfloat16, device="cuda:0")
+    out = {}
+    for label, shadow, bpe in (("fp32", None, 12), ("fp32_with_bf16_shadow", sh, 14)):
+        for _ in range(3):
+            prsgd.prsgd_sgd_update(x, g, 1e-3, shadow=shadow)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(reps):
+            prsgd.prsgd_sgd_update(x, g, 1e-3, shadow=shadow)
+        stop.record()
+        torch.cuda.synchronize()
+        sec = start.elapsed_time(stop) * 1e-3 / reps
+        out[label] = {"bytes": bpe * n_elems, "avg_us": 1e6 * sec, "GBps": bpe * n_elems / sec / 1e9,
+                      "frac_of_hbm_peak": bpe * n_elems / sec / 1e9 / HBM_PEAK_GBPS}
+    out["symbol"] = "update_kernel"
+    return out
 
 
 def main() -> int:
@@ -156,6 +196,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--interval", type=int, default=None)
     ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
+    ap.add_argument("--eager-restart", action="store_true",
+                    help="restart with the averaging kernel that overwrites every replica at once")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-average", action="store_true",
                     help="skip the extra HBM-scale timing of the averaging kernel")
@@ -210,6 +252,8 @@ def main() -> int:
     with torch.cuda.stream(stream):
         h = drivers.open_workload(w, inp, device="cuda:0", fused_update=not args.unfused,
                                   stream=stream)
+    if args.eager_restart:
+        prsgd.prsgd_set_lazy_restart(h, False)
     torch.cuda.synchronize()
 
     prsgd.prsgd_run(h, warmup, w.interval)
@@ -234,7 +278,7 @@ def main() -> int:
     kernels = {}
     for s in stats:
         per_iter = work.get(s["name"], {"bytes": 0, "flops": 0})
-        calls = prof_steps if s["name"] != "average" else max(1, prof_steps // w.interval)
+        calls = prof_steps if s["name"] not in ("average", "restart_mean") else max(1, prof_steps // w.interval)
         if s["name"] in ("lsq_steps", "mlp2_epoch"):
             calls = prof_steps                        # one launch covers several iterations
         tot_bytes, tot_flops = per_iter["bytes"] * calls, per_iter["flops"] * calls
@@ -261,11 +305,14 @@ def main() -> int:
                  "algorithmic_bytes_per_launch": kd["bytes_per_launch"],
                  "algorithmic_flops_per_launch": kd["flops_per_launch"]})
 
-    avg = kernels.get("average")
     restart = None
-    if avg:
-        restart = {"GBps": avg["GBps"], "frac_of_hbm_peak": avg["GBps"] / HBM_PEAK_GBPS,
-                   "avg_us": avg["avg_us"], "bytes": avg["bytes_per_launch"]}
+    for label in ("restart_mean", "average"):
+        avg = kernels.get(label)
+        if avg:
+            restart = {"kernel": label, "symbol": KERNEL_SYMBOL[label], "GBps": avg["GBps"],
+                       "frac_of_hbm_peak": avg["GBps"] / HBM_PEAK_GBPS, "avg_us": avg["avg_us"],
+                       "bytes": avg["bytes_per_launch"]}
+            break
 
     out = {
         "metric": "samples/sec across N replicas at interval I; restart-average HBM GB/s",
@@ -279,7 +326,8 @@ def main() -> int:
             w.name, w.model, "-".join(str(d) for d in w.dims), w.n_workers, w.batch, w.interval,
             w.rows_per_worker, w.lr, w.activation),
             "n_workers": w.n_workers, "batch": w.batch, "interval": w.interval,
-            "fused_update": not args.unfused, "last_minibatch_loss": loss},
+            "fused_update": not args.unfused, "deferred_broadcast": not args.eager_restart,
+            "last_minibatch_loss": loss},
         "roofline": roof,
         "restart_average": restart,
         "kernels": {k: {"avg_us": round(v["avg_us"], 3), "launches": v["launches"],
@@ -292,6 +340,7 @@ def main() -> int:
         # this workload's replicas are cache-resident: also report the kernel at HBM scale
         out["restart_average_hbm"] = restart_average_at_hbm_scale(prsgd, drivers, get_workload,
                                                                   make_inputs)
+        out["sgd_update_hbm"] = standalone_update_at_hbm_scale(prsgd)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))

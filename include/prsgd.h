@@ -108,8 +108,22 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k);
  */
 int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host /* [N] */);
 
-/* Restart: x_i <- (1/N) sum_j x_j for every i (eq. 2); workers summed in ascending order. */
+/*
+ * Restart: x_i <- (1/N) sum_j x_j for every i (eq. 2); workers summed in ascending order.
+ * After the call every worker's point (as seen by prsgd_read_params and by the next local
+ * iteration) is the node average.  By default the broadcast is deferred where the kernels
+ * support it: the average is written once and the next local iteration, which rewrites every
+ * replica anyway (x_i = ybar - gamma G_i, the form of eq. 2), reads it as the common starting
+ * point -- what the first footnote of Section 1 describes for I = 1.  Calling it again before
+ * any local step is a no-op.
+ */
 int prsgd_average(prsgd_ctx* ctx);
+/*
+ * on = 0: every prsgd_average overwrites all replicas at once (one read and one write of the
+ * whole replica set: the stand-alone averaging kernel).  on = 1 (default): deferred broadcast.
+ * Results are identical either way.
+ */
+int prsgd_set_lazy_restart(prsgd_ctx* ctx, int32_t on);
 
 /*
  * Algorithm 1 for `iterations` iterations from the current counter t: local steps, and an

@@ -100,7 +100,9 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   const uint16_t* d_g = p.d + (size_t)g * p.d_gs;
   float* w_g = p.params + (size_t)g * p.p_gs + p.w_off;
   uint16_t* s_g = p.shadow + (size_t)g * p.p_gs + p.w_off;
+  const float* wsrc_g = p.src + (size_t)g * p.src_gs + p.w_off;     // old weights
   const bool nt = p.streaming != 0;
+  const bool nt_read = nt && p.src_gs != 0;      // a shared source is re-read by every replica
 
   // ---- staging helpers ---------------------------------------------------------------------
   // B x 64 bf16 panel (H^T columns or a D tile): MB 16-byte vectors per thread, row = q*32 + tid/8
@@ -130,8 +132,8 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
     for (int q = 0; q < 4; ++q) {
       const int k = k0 + q * 16 + (tid >> 4), n = n0 + 4 * (tid & 15);
       const bool ok = k < p.K && n < p.Nn;
-      const f32x4_t* src = reinterpret_cast<const f32x4_t*>(w_g + (ok ? (size_t)k * p.ldw + n : (size_t)0));
-      reg[q] = nt ? __builtin_nontemporal_load(src) : *src;
+      const f32x4_t* src = reinterpret_cast<const f32x4_t*>(wsrc_g + (ok ? (size_t)k * p.ldw + n : (size_t)0));
+      reg[q] = nt_read ? __builtin_nontemporal_load(src) : *src;
       mask |= (ok ? 1u : 0u) << q;
     }
     return mask;
@@ -246,8 +248,8 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
     }
     if (bias_turn && tid < BN && n0 + tid < p.Nn) {
       const float cs = ((Bs[tid] + Bs[BN + tid]) + Bs[2 * BN + tid]) + Bs[3 * BN + tid];
-      float* bptr = p.params + (size_t)g * p.p_gs + p.b_off + n0 + tid;
-      *bptr = fmaf(-p.lr, cs, *bptr);
+      const float b_old = p.src[(size_t)g * p.src_gs + p.b_off + n0 + tid];
+      p.params[(size_t)g * p.p_gs + p.b_off + n0 + tid] = fmaf(-p.lr, cs, b_old);
     }
     if (it + S < n_t) wm = fetch_w(wr, n0 + S * BN);
   };

@@ -81,12 +81,18 @@ __global__ __launch_bounds__(kThreads) void average_kernel(f32x4_t* __restrict__
   }
 }
 
+// Node average into a separate vector (and its bf16 image): the replicas are only read.
+template <bool SHADOW, bool NT>
 __global__ __launch_bounds__(kThreads) void mean_kernel(const f32x4_t* __restrict__ params,
-                                                        f32x4_t* __restrict__ out, size_t stride4, int n,
-                                                        float n_f) {
+                                                        f32x4_t* __restrict__ out,
+                                                        u32x2_t* __restrict__ out_shadow, size_t stride4,
+                                                        int n, float n_f) {
   for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
-       col += (size_t)gridDim.x * kThreads)
-    out[col] = replica_sum<true>(params, stride4, col, n) / n_f;
+       col += (size_t)gridDim.x * kThreads) {
+    const f32x4_t mean = replica_sum<NT>(params, stride4, col, n) / n_f;
+    out[col] = mean;
+    if (SHADOW) out_shadow[col] = pack_bf16x4(mean);
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void broadcast_kernel(const float4* __restrict__ src,
@@ -201,11 +207,21 @@ hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_wor
   return hipGetLastError();
 }
 
-hipError_t launch_mean(const float* params, float* out, long m_pad, int n_workers, hipStream_t s) {
+hipError_t launch_mean(const float* params, float* out, uint16_t* out_shadow, long m_pad, int n_workers,
+                       bool streaming, hipStream_t s) {
   const size_t stride4 = (size_t)m_pad / 4;
-  hipLaunchKernelGGL(mean_kernel, dim3(grid_for(stride4, kStreamBlocks)), dim3(kThreads), 0, s,
-                     reinterpret_cast<const f32x4_t*>(params), reinterpret_cast<f32x4_t*>(out), stride4,
-                     n_workers, (float)n_workers);
+  const int grid = grid_for(stride4, 65536);
+  const f32x4_t* p4 = reinterpret_cast<const f32x4_t*>(params);
+  f32x4_t* o4 = reinterpret_cast<f32x4_t*>(out);
+  u32x2_t* s2 = reinterpret_cast<u32x2_t*>(out_shadow);
+  const float n_f = (float)n_workers;
+  if (out_shadow != nullptr) {
+    if (streaming) hipLaunchKernelGGL((mean_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
+    else hipLaunchKernelGGL((mean_kernel<true, false>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
+  } else {
+    if (streaming) hipLaunchKernelGGL((mean_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
+    else hipLaunchKernelGGL((mean_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
+  }
   return hipGetLastError();
 }
 

@@ -81,6 +81,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   int* flag = rows_next + MR;                              // [1] abort broadcast
 
   float* prm = p.params + (size_t)i * p.m_pad;
+  const float* prm0 = p.src + (size_t)i * p.src_stride;      // this worker's starting point
   const float* feat = p.features + (size_t)i * p.rows * d0;
   const int32_t* lab = p.labels + (size_t)i * p.rows;
 
@@ -95,16 +96,16 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       for (int s = 0; s < 4; ++s) {
         const int k = 16 * kb + 4 * q4 + s;
         const bool ok = kb < KB && k < d0;
-        const float v = prm[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
+        const float v = prm0[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
         w1[kbi][nt][s] = ok ? v : 0.0f;
       }
   }
   for (int e = tid; e < W * D2P; e += kThreads) {
     const int n = e / D2P, c = e % D2P;
-    w2[e] = c < d2 ? prm[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
+    w2[e] = c < d2 ? prm0[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
   }
-  if (tid < W) b1[tid] = prm[p.b1_off + j * W + tid];
-  if (tid < D2P) b2[tid] = tid < d2 ? prm[p.b2_off + tid] : 0.0f;
+  if (tid < W) b1[tid] = prm0[p.b1_off + j * W + tid];
+  if (tid < D2P) b2[tid] = tid < d2 ? prm0[p.b2_off + tid] : 0.0f;
   for (int e = tid; e < MR * ldx; e += kThreads) X[e] = 0.0f;     // pad rows / columns stay zero
   if (tid == 0) flag[0] = 0;
   __syncthreads();

@@ -405,7 +405,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   }
 
   const float* bias = (p.epi == EPI_FWD_HIDDEN || p.epi == EPI_FWD_LOGITS)
-                          ? p.params + pg + p.b_off : nullptr;
+                          ? p.bias_src + (size_t)g * p.bias_gs + p.b_off : nullptr;
   const E* aux = reinterpret_cast<const E*>(p.aux) + (size_t)g * p.aux_gs;
 #pragma unroll
   for (int i = 0; i < TM; ++i)

@@ -14,8 +14,8 @@ static int ilog2_rows(long n) {
 }
 
 __global__ __launch_bounds__(kThreads) void lsq_steps_kernel(
-    const float* __restrict__ features, const float* __restrict__ targets, float* __restrict__ params,
-    float* __restrict__ losses, int32_t* __restrict__ idx, int d, long m_pad, long rows, int log2n,
+    const float* __restrict__ features, const float* __restrict__ targets, const float* src,
+    long src_stride, float* params, float* __restrict__ losses, int32_t* __restrict__ idx, int d, long m_pad, long rows, int log2n,
     int batch, float lr, uint64_t seed, uint64_t t0, int k, const int* __restrict__ worker_steps) {
   extern __shared__ float lds[];
   float* x = lds;                                   // [d]
@@ -31,7 +31,8 @@ __global__ __launch_bounds__(kThreads) void lsq_steps_kernel(
   float* x_glob = params + (size_t)i * m_pad;
   const float inv_b = 1.0f / (float)batch;
 
-  for (int c = tid; c < d; c += kThreads) x[c] = x_glob[c];
+  const float* x_start = src + (size_t)i * src_stride;     // the replica, or the shared node average
+  for (int c = tid; c < d; c += kThreads) x[c] = x_start[c];
   float loss = 0.0f;
 
   for (int s = 1; s <= my_k; ++s) {
@@ -67,14 +68,15 @@ __global__ __launch_bounds__(kThreads) void lsq_steps_kernel(
   if (tid == 0) losses[i] = loss;
 }
 
-hipError_t launch_lsq_steps(const float* features, const float* targets, float* params, float* losses,
+hipError_t launch_lsq_steps(const float* features, const float* targets, const float* src,
+                            long src_stride, float* params, float* losses,
                             int32_t* idx, int n_workers, int d, long m_pad, long rows, int batch,
                             float lr, uint64_t seed, int64_t t0, int k, const int* worker_steps,
                             hipStream_t s) {
   if (k <= 0) return hipSuccess;
   const size_t lds_bytes = ((size_t)d + 2 * (size_t)batch) * sizeof(float);
   hipLaunchKernelGGL(lsq_steps_kernel, dim3(n_workers), dim3(kThreads), lds_bytes, s, features, targets,
-                     params, losses, idx, d, m_pad, rows, ilog2_rows(rows), batch, lr, seed,
+                     src, src_stride, params, losses, idx, d, m_pad, rows, ilog2_rows(rows), batch, lr, seed,
                      (uint64_t)t0, k, worker_steps);
   return hipGetLastError();
 }

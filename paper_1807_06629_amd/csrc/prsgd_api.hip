@@ -17,7 +17,7 @@ namespace prsgd {
 const char* kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
                                         "sgd_update", "average", "mean",       "broadcast", "lsq_steps",
-                                        "mlp2_epoch", "gemm_bwd"};
+                                        "mlp2_epoch", "gemm_bwd", "restart_mean"};
   return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
 }
 }  // namespace prsgd
@@ -30,7 +30,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local char g_init_error[256] = "";
 
 struct Carve {
-  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, steps = 0;
+  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, mean_shadow = 0, steps = 0;
   size_t h[PRSGD_MAX_DIMS] = {0}, delta[PRSGD_MAX_DIMS] = {0};
   size_t total = 0;
 };
@@ -99,7 +99,10 @@ void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
     }
     cv->delta[L] = take(n * b * lo.ld[L] * es);
     cv->logits = take(n * b * lo.ld[L] * 4);
-    if (bf16) cv->shadow = take(n * (size_t)lo.m_pad * 2);
+    if (bf16) {
+      cv->shadow = take(n * (size_t)lo.m_pad * 2);
+      cv->mean_shadow = take((size_t)lo.m_pad * 2);
+    }
     if (L == 2 && !bf16 && c->fused_update && (lo.d[1] % 16) == 0 && lo.d[2] <= 64 && c->batch <= 64) {
       // epoch kernel: partial logits for the finest team split, arrival counters, abort flag
       // batch tiles come in 1, 2 or 4 blocks of 16 rows
@@ -125,6 +128,9 @@ struct prsgd_ctx {
   bool use_fused2;      // one-hidden-layer fp32 MLP: whole epochs in one launch
   Fused2Plan f2;
   bool streaming;       // replica set >= 1 GiB: weight traffic bypasses the last-level cache
+  bool lazy_restart;    // a restart only writes the node average; the next local iteration
+                        // reads it as every worker's starting point (no broadcast)
+  bool at_mean;         // the replicas are stale: every worker's current point is the vector `mean`
   hipStream_t stream;
   const float* features;
   const void* targets;
@@ -144,6 +150,16 @@ struct prsgd_ctx {
 
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   uint16_t* shadow() const { return bf16 ? at<uint16_t>(cv.shadow) : nullptr; }
+  float* mean() const { return at<float>(cv.mean); }
+  uint16_t* mean_shadow() const { return bf16 ? at<uint16_t>(cv.mean_shadow) : nullptr; }
+  // where a worker's current point is read from, and the stride between workers
+  const float* src() const { return at_mean ? mean() : params; }
+  long src_stride() const { return at_mean ? 0 : lo.m_pad; }
+  // configurations whose first local iteration can start from the shared node average
+  bool can_start_from_mean() const {
+    return cfg.model == PRSGD_LSQ || use_fused2 ||
+           (bf16 && cfg.fused_update && prsgd::bwd_fused_supported(cfg.batch));
+  }
   float* grads() const { return cfg.fused_update ? nullptr : at<float>(cv.grads); }
 };
 
@@ -202,6 +218,8 @@ struct Timed {
     if (e_ != hipSuccess) return hip_fail(ctx, e_, kernel_kind_name(kind)); \
   } while (0)
 
+int materialize(prsgd_ctx* ctx);
+
 // One local iteration of every (active) MLP worker: gradient observation + eq. (3).
 int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
   const prsgd_config& c = ctx->cfg;
@@ -232,8 +250,21 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
   auto act_in = [&](int l) -> const void* {   // H_l as stored (l = 0: the gathered batch)
     return l == 0 ? ctx->at<void>(cv.xb) : ctx->at<void>(cv.h[l]);
   };
+  const bool fused_bwd = bf16 && c.fused_update && bwd_fused_supported(B);
+  // Right after a restart every worker starts from the shared node average (stride 0); only
+  // the fused backward kernel writes complete replicas from it, so every other path first
+  // broadcasts the average.  A masked worker (Algorithm 3) would keep a stale replica.
+  if (ctx->at_mean && (!fused_bwd || worker_steps != nullptr)) {
+    const int rc = materialize(ctx);
+    if (rc != PRSGD_OK) return rc;
+  }
+  const bool from_mean = ctx->at_mean;
+  const long w_gs = from_mean ? 0 : lo.m_pad;
   // The matrix products read weights from the bf16 shadow (bf16 mode) or the fp32 master.
-  const void* wsrc = bf16 ? (const void*)ctx->shadow() : (const void*)ctx->params;
+  const void* wsrc = bf16 ? (const void*)(from_mean ? ctx->mean_shadow() : ctx->shadow())
+                          : (const void*)ctx->params;
+  base.bias_src = ctx->src();
+  base.bias_gs = ctx->src_stride();
 
   // forward
   for (int l = 1; l <= L; ++l) {
@@ -241,7 +272,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
     p.a = act_in(l - 1); p.a_gs = (long)B * lo.ld[l - 1]; p.lda = lo.ld[l - 1];
     p.b = bf16 ? (const void*)(reinterpret_cast<const uint16_t*>(wsrc) + lo.w_off[l - 1])
                : (const void*)(reinterpret_cast<const float*>(wsrc) + lo.w_off[l - 1]);
-    p.b_gs = lo.m_pad; p.ldb = lo.ld[l];
+    p.b_gs = w_gs; p.ldb = lo.ld[l];
     p.M = B; p.N = lo.d[l]; p.Kc = lo.d[l - 1];
     p.b_off = lo.b_off[l - 1];
     p.out_gs = (long)B * lo.ld[l]; p.ldo = lo.ld[l]; p.out_cols = lo.ld[l];
@@ -257,13 +288,13 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
 
   // backward.  bf16 operands with the fused update: one kernel per layer does the weight
   // gradient, eq. (3) and the delta of the layer below in a single pass over W_l.
-  const bool fused_bwd = bf16 && c.fused_update && bwd_fused_supported(B);
   for (int l = L; fused_bwd && l >= 1; --l) {
     BwdArgs q;
     memset(&q, 0, sizeof(q));
     q.h = reinterpret_cast<const uint16_t*>(act_in(l - 1)); q.h_gs = (long)B * lo.ld[l - 1]; q.ldh = lo.ld[l - 1];
     q.d = ctx->at<uint16_t>(cv.delta[l]); q.d_gs = (long)B * lo.ld[l]; q.ldd = lo.ld[l];
     q.params = ctx->params; q.shadow = ctx->shadow(); q.p_gs = lo.m_pad;
+    q.src = ctx->src(); q.src_gs = ctx->src_stride();
     q.w_off = lo.w_off[l - 1]; q.b_off = lo.b_off[l - 1]; q.ldw = lo.ld[l];
     if (l > 1) { q.dx = ctx->at<uint16_t>(cv.delta[l - 1]); q.dx_gs = (long)B * lo.ld[l - 1]; q.lddx = lo.ld[l - 1]; }
     q.B = B; q.K = lo.d[l - 1]; q.Nn = lo.d[l];
@@ -304,6 +335,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
       LAUNCH(ctx, KK_UPDATE, launch_update_masked(ctx->params, ctx->grads(), ctx->shadow(), lo.m_pad,
                                                   N, ctx->lr, worker_steps, step, s));
   }
+  ctx->at_mean = false;            // every parameter of every replica has been rewritten
   return PRSGD_OK;
 }
 
@@ -315,6 +347,8 @@ Fused2Args fused2_args(prsgd_ctx* ctx, int k, const int* worker_steps) {
   a.features = ctx->features;
   a.labels = reinterpret_cast<const int32_t*>(ctx->targets);
   a.params = ctx->params;
+  a.src = ctx->src();
+  a.src_stride = ctx->src_stride();
   a.m_pad = lo.m_pad;
   a.w1_off = lo.w_off[0]; a.b1_off = lo.b_off[0]; a.w2_off = lo.w_off[1]; a.b2_off = lo.b_off[1];
   a.ld1 = lo.ld[1]; a.ld2 = lo.ld[2];
@@ -347,6 +381,16 @@ int check_fused2_abort(prsgd_ctx* ctx) {
   if (e != hipSuccess) return hip_fail(ctx, e, "abort-flag read");
   if (flag != 0)
     return set_err(ctx, PRSGD_ESTATE, "epoch kernel gave up waiting for a team member; parameters are invalid");
+  return PRSGD_OK;
+}
+
+// Writes the node average into every replica (and the bf16 shadow) if the last restart left the
+// replicas stale.
+int materialize(prsgd_ctx* ctx) {
+  if (!ctx->at_mean) return PRSGD_OK;
+  LAUNCH(ctx, KK_BROADCAST, launch_broadcast(ctx->mean(), ctx->params, ctx->shadow(), ctx->lo.m_pad,
+                                             ctx->cfg.n_workers, ctx->stream));
+  ctx->at_mean = false;
   return PRSGD_OK;
 }
 
@@ -433,6 +477,8 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   ctx->params = reinterpret_cast<float*>(params_dev);
   ctx->ws = reinterpret_cast<char*>(workspace_dev);
   ctx->t = 0;
+  ctx->lazy_restart = true;
+  ctx->at_mean = false;
   ctx->lr = cfg->lr;
   ctx->err[0] = 0;
   ctx->profiling = false;
@@ -471,16 +517,22 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
   if (k < 0) return set_err(ctx, PRSGD_EINVAL, "k must be >= 0");
   const prsgd_config& c = ctx->cfg;
   if (c.model == PRSGD_LSQ) {
+    if (k == 0) return PRSGD_OK;
     LAUNCH(ctx, KK_LSQ,
-           launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->params,
+           launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->src(),
+                            ctx->src_stride(), ctx->params,
                             ctx->at<float>(ctx->cv.losses), ctx->at<int32_t>(ctx->cv.idx), c.n_workers,
                             ctx->lo.d[0], ctx->lo.m_pad, (long)c.rows_per_worker, c.batch, ctx->lr, c.seed,
                             ctx->t, k, nullptr, ctx->stream));
+    ctx->at_mean = false;
     ctx->t += k;
     return PRSGD_OK;
   }
   if (ctx->use_fused2) {
-    if (k > 0) LAUNCH(ctx, KK_FUSED2, launch_fused2(ctx->f2, fused2_args(ctx, k, nullptr), ctx->stream));
+    if (k > 0) {
+      LAUNCH(ctx, KK_FUSED2, launch_fused2(ctx->f2, fused2_args(ctx, k, nullptr), ctx->stream));
+      ctx->at_mean = false;
+    }
     ctx->t += k;
     return PRSGD_OK;
   }
@@ -501,6 +553,9 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
     if (steps_host[i] < 0) return set_err(ctx, PRSGD_EINVAL, "worker step counts must be >= 0");
     if (steps_host[i] > k_max) k_max = steps_host[i];
   }
+  // a worker that takes no step must still hold the restart point: broadcast it first
+  const int mrc = materialize(ctx);
+  if (mrc != PRSGD_OK) return mrc;
   int* steps_dev = ctx->at<int>(ctx->cv.steps);
   // The pageable source may be reused by the caller right after return: wait for the copy.
   hipError_t e = hipMemcpyAsync(steps_dev, steps_host, sizeof(int32_t) * c.n_workers,
@@ -510,6 +565,7 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
   if (c.model == PRSGD_LSQ) {
     LAUNCH(ctx, KK_LSQ,
            launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->params,
+                            ctx->lo.m_pad, ctx->params,
                             ctx->at<float>(ctx->cv.losses), ctx->at<int32_t>(ctx->cv.idx), c.n_workers,
                             ctx->lo.d[0], ctx->lo.m_pad, (long)c.rows_per_worker, c.batch, ctx->lr, c.seed,
                             ctx->t, k_max, steps_dev, ctx->stream));
@@ -532,9 +588,29 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
 
 int prsgd_average(prsgd_ctx* ctx) {
   if (ctx == nullptr) return PRSGD_EINVAL;
+  if (ctx->at_mean) return PRSGD_OK;        // all workers already sit at their node average
+  if (ctx->lazy_restart && ctx->can_start_from_mean()) {
+    // eq. (2) without the broadcast: ybar is written once; the next local iteration reads it as
+    // every worker's starting point and writes the replicas  x_i = ybar - gamma G_i  itself
+    LAUNCH(ctx, KK_RESTART_MEAN,
+           launch_mean(ctx->params, ctx->mean(), ctx->mean_shadow(), ctx->lo.m_pad, ctx->cfg.n_workers,
+                       ctx->streaming, ctx->stream));
+    ctx->at_mean = true;
+    return PRSGD_OK;
+  }
   LAUNCH(ctx, KK_AVERAGE,
          launch_average(ctx->params, ctx->shadow(), ctx->lo.m_pad, ctx->cfg.n_workers, ctx->streaming,
                         ctx->stream));
+  return PRSGD_OK;
+}
+
+int prsgd_set_lazy_restart(prsgd_ctx* ctx, int32_t on) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (!on) {
+    const int rc = materialize(ctx);
+    if (rc != PRSGD_OK) return rc;
+  }
+  ctx->lazy_restart = on != 0;
   return PRSGD_OK;
 }
 
@@ -564,10 +640,12 @@ int prsgd_read_params(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m)
   const int arc = check_fused2_abort(ctx);
   if (arc != PRSGD_OK) return arc;
   const float* src;
-  if (worker < 0) {
-    LAUNCH(ctx, KK_MEAN, launch_mean(ctx->params, ctx->at<float>(ctx->cv.mean), ctx->lo.m_pad,
-                                     ctx->cfg.n_workers, ctx->stream));
-    src = ctx->at<float>(ctx->cv.mean);
+  if (ctx->at_mean) {
+    src = ctx->mean();                      // every worker's point, and their average
+  } else if (worker < 0) {
+    LAUNCH(ctx, KK_MEAN, launch_mean(ctx->params, ctx->mean(), nullptr, ctx->lo.m_pad,
+                                     ctx->cfg.n_workers, true, ctx->stream));
+    src = ctx->mean();
   } else {
     src = ctx->params + (size_t)worker * ctx->lo.m_pad;
   }
@@ -584,6 +662,11 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
   if (in_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "in_host is null");
   if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
   if (worker < -1 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
+  if (worker >= 0) {                        // the other replicas must hold their restart point
+    const int mrc = materialize(ctx);
+    if (mrc != PRSGD_OK) return mrc;
+  }
+  ctx->at_mean = false;
   pad_from_dense(ctx, in_host, ctx->host_pad.data());
   const size_t bytes = sizeof(float) * (size_t)ctx->lo.m_pad;
   hipError_t e;

@@ -50,6 +50,9 @@ struct GemmArgs {
   float lr;
   // parameters / gradients (fp32, replica stride m_pad), bf16 shadow of the parameters
   float* params; float* grads; uint16_t* shadow; long p_gs;
+  // where the forward products read the bias from: the replicas, or (right after a restart
+  // whose broadcast was skipped) the shared node average with stride 0
+  const float* bias_src; long bias_gs;
   long w_off, b_off; int ldw;
   // activation-like output (element type T, or float for logits) and auxiliary input
   void* out; long out_gs; int ldo; int out_cols;
@@ -60,7 +63,7 @@ struct GemmArgs {
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
-  KK_LSQ, KK_FUSED2, KK_BWD, KK_COUNT
+  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_COUNT
 };
 
 // Fused backward step of one layer with bf16 operands (kernels_bwd.hip): weight gradient, local
@@ -69,6 +72,9 @@ struct BwdArgs {
   const uint16_t* h; long h_gs; int ldh;        // H_{l-1} [N][B][ldh]
   const uint16_t* d; long d_gs; int ldd;        // D_l     [N][B][ldd]
   float* params; uint16_t* shadow; long p_gs;   // fp32 master and bf16 shadow, replica stride
+  const float* src; long src_gs;                // where the old parameters are read from: the
+                                                // replicas (src_gs = p_gs) or the shared node
+                                                // average right after a restart (src_gs = 0)
   long w_off, b_off; int ldw;
   uint16_t* dx; long dx_gs; int lddx;           // D_{l-1} [N][B][lddx]; nullptr for the first layer
   int B, K, Nn;                                 // minibatch rows, d_{l-1}, d_l
@@ -88,6 +94,8 @@ struct Fused2Plan {
 struct Fused2Args {
   const float* features; const int32_t* labels;
   float* params; long m_pad; long w1_off, b1_off, w2_off, b2_off; int ld1, ld2;
+  const float* src; long src_stride;   // starting point of every worker: its replica, or the shared
+                                       // node average (stride 0) right after a restart
   int n_workers, P, d0, d1, d2, d2p, ldx, batch; long rows; int log2n;
   int act; float lr; uint64_t seed; uint64_t t0; int k;
   const int* worker_steps;       // Algorithm 3 step counts (nullptr: every worker takes k steps)
@@ -119,7 +127,8 @@ hipError_t launch_loss_mean(const float* row_loss, float* losses, int n_workers,
 
 hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, bool streaming,
                           hipStream_t s);
-hipError_t launch_mean(const float* params, float* out, long m_pad, int n_workers, hipStream_t s);
+hipError_t launch_mean(const float* params, float* out, uint16_t* out_shadow, long m_pad, int n_workers,
+                       bool streaming, hipStream_t s);
 hipError_t launch_broadcast(const float* src, float* params, uint16_t* shadow, long m_pad,
                             int n_workers, hipStream_t s);
 hipError_t launch_refresh_shadow(const float* params, uint16_t* shadow, long count, hipStream_t s);
@@ -129,7 +138,8 @@ hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t coun
 hipError_t launch_update_masked(float* x, const float* g, uint16_t* shadow, long m_pad, int n_workers,
                                 float lr, const int* worker_steps, int step, hipStream_t s);
 
-hipError_t launch_lsq_steps(const float* features, const float* targets, float* params, float* losses,
+hipError_t launch_lsq_steps(const float* features, const float* targets, const float* src,
+                            long src_stride, float* params, float* losses,
                             int32_t* idx, int n_workers, int d, long m_pad, long rows, int batch,
                             float lr, uint64_t seed, int64_t t0, int k, const int* worker_steps,
                             hipStream_t s);

@@ -66,6 +66,7 @@ def _load() -> ctypes.CDLL:
         "prsgd_local_steps": (ctypes.c_int, [vp, i32]),
         "prsgd_local_steps_hetero": (ctypes.c_int, [vp, vp]),
         "prsgd_average": (ctypes.c_int, [vp]),
+        "prsgd_set_lazy_restart": (ctypes.c_int, [vp, i32]),
         "prsgd_run": (ctypes.c_int, [vp, i64, i32]),
         "prsgd_read_params": (ctypes.c_int, [vp, i32, vp, sz]),
         "prsgd_write_params": (ctypes.c_int, [vp, i32, vp, sz]),
@@ -198,6 +199,10 @@ def prsgd_local_steps_hetero(h: Handle, steps: Sequence[int]) -> None:
 
 def prsgd_average(h: Handle) -> None:
     _check(_lib.prsgd_average(h.ctx), h.ctx)
+
+
+def prsgd_set_lazy_restart(h: Handle, on: bool) -> None:
+    _check(_lib.prsgd_set_lazy_restart(h.ctx, 1 if on else 0), h.ctx)
 
 
 def prsgd_run(h: Handle, iterations: int, interval: int) -> None:

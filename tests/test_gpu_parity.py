@@ -370,6 +370,74 @@ def test_restart_average_properties(P, D, n_workers):
     P.prsgd_destroy(h)
 
 
+LAZY_CASES = [
+    ("lsq", dict()),
+    ("epoch", dict(dims=(64, 32, 10), batch=8, n_workers=3)),
+    ("bf16", dict(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="relu")),
+    ("fp32-layers", dict(dims=(40, 24, 16, 6), batch=6, n_workers=3)),   # no deferred broadcast: falls back
+]
+
+
+def _lazy_workload(kind, kw):
+    if kind == "lsq":
+        return get_workload("c1").scaled(rows_per_worker=128, n_workers=3, iterations=9, interval=2)
+    return small_mlp(rows_per_worker=128, iterations=9, interval=2, **kw)
+
+
+@pytest.mark.parametrize("kind,kw", LAZY_CASES)
+@pytest.mark.parametrize("interval", [1, 2])
+def test_deferred_broadcast_gives_the_same_run_as_the_averaging_kernel(P, D, kind, kw, interval):
+    w = _lazy_workload(kind, kw)
+    inp = make_inputs(w)
+    outs = []
+    for lazy in (True, False):
+        h = _open(D, w, inp)
+        P.prsgd_set_lazy_restart(h, lazy)
+        names = _kernel_names(P, h, w.iterations, interval)
+        if kind != "fp32-layers":
+            assert ("restart_mean" in names) == lazy and ("average" in names) == (not lazy), names
+            if lazy and interval == 1:
+                assert "broadcast" not in names          # the replicas are never broadcast
+        xs, xbar = D.read_all(h), P.prsgd_read_params(h, -1)
+        outs.append((xs, xbar, P.prsgd_read_loss(h)))
+        P.prsgd_destroy(h)
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+    want = oracle_run(w, inp, interval=interval)
+    tol = 5e-3 if kind == "bf16" else 1e-4
+    assert rel_err(outs[0][0], want["x"]) <= tol
+
+
+def test_state_right_after_a_deferred_restart(P, D):
+    w = small_mlp(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="relu",
+                  rows_per_worker=128)
+    inp = inputs_for(w)
+    h = _open(D, w, inp)
+    P.prsgd_local_steps(h, 3)
+    xbar = P.prsgd_read_params(h, -1)
+    P.prsgd_average(h)
+    P.prsgd_average(h)                                   # second call: nothing to do
+    for i in range(w.n_workers):                         # every worker sits at the average
+        assert np.array_equal(P.prsgd_read_params(h, i), xbar)
+    assert np.array_equal(P.prsgd_read_params(h, -1), xbar)
+    # overwriting one replica keeps the others at the restart point
+    other = (xbar * np.float32(0.5)).astype(np.float32)
+    P.prsgd_write_params(h, 1, other)
+    got = D.read_all(h)
+    assert np.array_equal(got[1], other) and np.array_equal(got[0], xbar) and np.array_equal(got[3], xbar)
+    P.prsgd_destroy(h)
+    # Algorithm 3 right after a deferred restart: a worker with zero steps keeps the average
+    h = _open(D, w, inp)
+    P.prsgd_local_steps(h, 2)
+    P.prsgd_average(h)
+    xbar = P.prsgd_read_params(h, -1)
+    P.prsgd_local_steps_hetero(h, [2, 0, 1, 0])
+    got = D.read_all(h)
+    assert np.array_equal(got[1], xbar) and np.array_equal(got[3], xbar)
+    assert not np.array_equal(got[0], xbar)
+    P.prsgd_destroy(h)
+
+
 def test_interval_one_is_minibatch_sgd_on_the_gpu(P, D):
     w = small_mlp(dims=(40, 24, 6), batch=6, n_workers=4, iterations=12, interval=1)
     inp = inputs_for(w)
