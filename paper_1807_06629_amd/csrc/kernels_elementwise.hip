@@ -41,42 +41,78 @@ __device__ __forceinline__ u32x2_t pack_bf16x4(f32x4_t v) {
   return r;
 }
 
-// Sum of column `col` (16-byte index) over the replicas, ascending i.
-template <bool NT>
-__device__ __forceinline__ f32x4_t replica_sum(const f32x4_t* __restrict__ p, size_t stride4, size_t col,
-                                               int n) {
-  f32x4_t s = ld4<NT>(p + col);
-  int i = 1;
+// Sums of U columns (16-byte indices col[u]) over the replicas, ascending i, kChunk x U loads in
+// flight.
+template <bool NT, int U>
+__device__ __forceinline__ void replica_sums(const f32x4_t* __restrict__ p, size_t stride4,
+                                             const size_t (&col)[U], int n, f32x4_t (&s)[U]) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) s[u] = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+  int i = 0;
   for (; i + kChunk <= n; i += kChunk) {
-    f32x4_t v[kChunk];
+    f32x4_t v[kChunk][U];
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) v[u] = ld4<NT>(p + (size_t)(i + u) * stride4 + col);
+    for (int c = 0; c < kChunk; ++c)
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) s += v[u];
+      for (int u = 0; u < U; ++u) v[c][u] = ld4<NT>(p + (size_t)(i + c) * stride4 + col[u]);
+#pragma unroll
+    for (int c = 0; c < kChunk; ++c)
+#pragma unroll
+      for (int u = 0; u < U; ++u) s[u] += v[c][u];
   }
   if (i < n) {
-    f32x4_t v[kChunk];
+    // last, partial chunk without branches between the loads: a replica index past the end
+    // re-reads the last replica and contributes nothing
+    f32x4_t v[kChunk][U];
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u)
-      if (i + u < n) v[u] = ld4<NT>(p + (size_t)(i + u) * stride4 + col);
+    for (int c = 0; c < kChunk; ++c) {
+      const int r = i + c < n ? i + c : n - 1;
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u)
-      if (i + u < n) s += v[u];
+      for (int u = 0; u < U; ++u) v[c][u] = ld4<NT>(p + (size_t)r * stride4 + col[u]);
+    }
+#pragma unroll
+    for (int c = 0; c < kChunk; ++c) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) s[u] += (i + c < n) ? v[c][u] : (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+    }
   }
-  return s;
+}
+
+constexpr int kColsPerThread = 2;   // a workgroup takes contiguous chunks of 2 x 256 columns
+
+// Columns of this thread in the chunk that starts at `base`; a column beyond the end is replaced
+// by column 0 (its loads stay in bounds, its result is dropped).
+template <int U>
+__device__ __forceinline__ void chunk_columns(size_t base, size_t stride4, size_t (&col)[U], bool (&ok)[U]) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const size_t c = base + (size_t)u * kThreads + threadIdx.x;
+    ok[u] = c < stride4;
+    col[u] = ok[u] ? c : 0;
+  }
 }
 
 template <bool SHADOW, bool NT>
 __global__ __launch_bounds__(kThreads) void average_kernel(f32x4_t* __restrict__ params,
                                                            u32x2_t* __restrict__ shadow, size_t stride4,
                                                            int n, float n_f) {
-  for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
-       col += (size_t)gridDim.x * kThreads) {
-    const f32x4_t mean = replica_sum<NT>(params, stride4, col, n) / n_f;
-    for (int i = 0; i < n; ++i) st4<NT>(params + (size_t)i * stride4 + col, mean);
-    if (SHADOW) {
-      const u32x2_t h = pack_bf16x4(mean);
-      for (int i = 0; i < n; ++i) st2<NT>(shadow + (size_t)i * stride4 + col, h);
+  constexpr int U = kColsPerThread;
+  constexpr size_t kPer = (size_t)U * kThreads;
+  for (size_t base = (size_t)blockIdx.x * kPer; base < stride4; base += (size_t)gridDim.x * kPer) {
+    size_t col[U];
+    bool ok[U];
+    f32x4_t sum[U];
+    chunk_columns<U>(base, stride4, col, ok);
+    replica_sums<NT, U>(params, stride4, col, n, sum);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!ok[u]) continue;
+      const f32x4_t mean = sum[u] / n_f;
+      for (int i = 0; i < n; ++i) st4<NT>(params + (size_t)i * stride4 + col[u], mean);
+      if (SHADOW) {
+        const u32x2_t h = pack_bf16x4(mean);
+        for (int i = 0; i < n; ++i) st2<NT>(shadow + (size_t)i * stride4 + col[u], h);
+      }
     }
   }
 }
@@ -87,11 +123,21 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const f32x4_t* __restric
                                                         f32x4_t* __restrict__ out,
                                                         u32x2_t* __restrict__ out_shadow, size_t stride4,
                                                         int n, float n_f) {
-  for (size_t col = (size_t)blockIdx.x * kThreads + threadIdx.x; col < stride4;
-       col += (size_t)gridDim.x * kThreads) {
-    const f32x4_t mean = replica_sum<NT>(params, stride4, col, n) / n_f;
-    out[col] = mean;
-    if (SHADOW) out_shadow[col] = pack_bf16x4(mean);
+  constexpr int U = kColsPerThread;
+  constexpr size_t kPer = (size_t)U * kThreads;
+  for (size_t base = (size_t)blockIdx.x * kPer; base < stride4; base += (size_t)gridDim.x * kPer) {
+    size_t col[U];
+    bool ok[U];
+    f32x4_t sum[U];
+    chunk_columns<U>(base, stride4, col, ok);
+    replica_sums<NT, U>(params, stride4, col, n, sum);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!ok[u]) continue;
+      const f32x4_t mean = sum[u] / n_f;
+      out[col[u]] = mean;
+      if (SHADOW) out_shadow[col[u]] = pack_bf16x4(mean);
+    }
   }
 }
 
@@ -118,25 +164,38 @@ __global__ __launch_bounds__(kThreads) void refresh_shadow_kernel(const float4* 
     shadow[k] = pack_bf16x4(params[k]);
 }
 
-// x <- x - lr * g on float4 columns; `tail` scalars at the end when count % 4 != 0.
+// x <- x - lr * g on 16-byte vectors; `tail` scalars at the end when count % 4 != 0.  A workgroup
+// takes contiguous chunks of U x 256 vectors and issues all its loads before the first store.
+template <int U, bool NT>
 __global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ x,
                                                           const float* __restrict__ g,
                                                           uint16_t* __restrict__ shadow, size_t count,
                                                           float lr) {
   const size_t count4 = count / 4;
-  float4* x4 = reinterpret_cast<float4*>(x);
-  const float4* g4 = reinterpret_cast<const float4*>(g);
-  uint2* s4 = reinterpret_cast<uint2*>(shadow);
-  for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < count4;
-       k += (size_t)gridDim.x * kThreads) {
-    float4 xv = x4[k];
-    const float4 gv = g4[k];
-    xv.x = fmaf(-lr, gv.x, xv.x);
-    xv.y = fmaf(-lr, gv.y, xv.y);
-    xv.z = fmaf(-lr, gv.z, xv.z);
-    xv.w = fmaf(-lr, gv.w, xv.w);
-    x4[k] = xv;
-    if (shadow != nullptr) s4[k] = pack_bf16x4(xv);
+  f32x4_t* x4 = reinterpret_cast<f32x4_t*>(x);
+  const f32x4_t* g4 = reinterpret_cast<const f32x4_t*>(g);
+  u32x2_t* s4 = reinterpret_cast<u32x2_t*>(shadow);
+  constexpr size_t kPer = (size_t)U * kThreads;
+  for (size_t b = (size_t)blockIdx.x * kPer; b < count4; b += (size_t)gridDim.x * kPer) {
+    f32x4_t xv[U], gv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t k = b + (size_t)u * kThreads + threadIdx.x;
+      if (k < count4) { xv[u] = ld4<NT>(x4 + k); gv[u] = ld4<NT>(g4 + k); }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t k = b + (size_t)u * kThreads + threadIdx.x;
+      if (k < count4) {
+        f32x4_t w = xv[u];
+        w.x = fmaf(-lr, gv[u].x, w.x);
+        w.y = fmaf(-lr, gv[u].y, w.y);
+        w.z = fmaf(-lr, gv[u].z, w.z);
+        w.w = fmaf(-lr, gv[u].w, w.w);
+        st4<NT>(x4 + k, w);
+        if (shadow != nullptr) st2<NT>(s4 + k, pack_bf16x4(w));
+      }
+    }
   }
   if (blockIdx.x == 0 && threadIdx.x < (count & 3)) {
     const size_t k = count4 * 4 + threadIdx.x;
@@ -193,7 +252,7 @@ hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_wor
   // One column per thread in a single pass (measured best); the non-temporal variant is for
   // replica sets far beyond the 256 MB last-level cache.
   const bool nt = streaming;
-  const int grid = grid_for(stride4, 65536);
+  const int grid = grid_for((stride4 + kColsPerThread - 1) / kColsPerThread, 65536);
   f32x4_t* p4 = reinterpret_cast<f32x4_t*>(params);
   u32x2_t* s2 = reinterpret_cast<u32x2_t*>(shadow);
   const float n_f = (float)n_workers;
@@ -210,7 +269,7 @@ hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_wor
 hipError_t launch_mean(const float* params, float* out, uint16_t* out_shadow, long m_pad, int n_workers,
                        bool streaming, hipStream_t s) {
   const size_t stride4 = (size_t)m_pad / 4;
-  const int grid = grid_for(stride4, 65536);
+  const int grid = grid_for((stride4 + kColsPerThread - 1) / kColsPerThread, 65536);
   const f32x4_t* p4 = reinterpret_cast<const f32x4_t*>(params);
   f32x4_t* o4 = reinterpret_cast<f32x4_t*>(out);
   u32x2_t* s2 = reinterpret_cast<u32x2_t*>(out_shadow);
@@ -253,8 +312,12 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) 
 hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t count, float lr,
                          hipStream_t s) {
   if (count == 0) return hipSuccess;
-  hipLaunchKernelGGL(update_kernel, dim3(grid_for(count / 4 + 1, kStreamBlocks)), dim3(kThreads), 0, s,
-                     x, g, shadow, count, lr);
+  // vectors far beyond the 256 MB last-level cache are streamed with non-temporal accesses
+  const bool nt = count * sizeof(float) >= ((size_t)1 << 28);
+  constexpr int U = 4;
+  const int grid = grid_for((count / 4 + U - 1) / U + 1, 65536);
+  if (nt) hipLaunchKernelGGL((update_kernel<U, true>), dim3(grid), dim3(kThreads), 0, s, x, g, shadow, count, lr);
+  else hipLaunchKernelGGL((update_kernel<U, false>), dim3(grid), dim3(kThreads), 0, s, x, g, shadow, count, lr);
   return hipGetLastError();
 }
 
