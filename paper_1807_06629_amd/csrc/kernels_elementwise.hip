@@ -78,7 +78,10 @@ __device__ __forceinline__ void replica_sums(const f32x4_t* __restrict__ p, size
   }
 }
 
-constexpr int kColsPerThread = 2;   // a workgroup takes contiguous chunks of 2 x 256 columns
+// Columns per thread: a workgroup takes contiguous chunks of U x 256 columns.  Two columns keep
+// more loads in flight on replica sets that fill the machine; small ones need every workgroup
+// they can get and take one.
+constexpr size_t kTwoColumnsFrom = (size_t)2 * 256 * 2048;   // columns: >= 2048 workgroups at U = 2
 
 // Columns of this thread in the chunk that starts at `base`; a column beyond the end is replaced
 // by column 0 (its loads stay in bounds, its result is dropped).
@@ -92,11 +95,10 @@ __device__ __forceinline__ void chunk_columns(size_t base, size_t stride4, size_
   }
 }
 
-template <bool SHADOW, bool NT>
+template <bool SHADOW, bool NT, int U>
 __global__ __launch_bounds__(kThreads) void average_kernel(f32x4_t* __restrict__ params,
                                                            u32x2_t* __restrict__ shadow, size_t stride4,
                                                            int n, float n_f) {
-  constexpr int U = kColsPerThread;
   constexpr size_t kPer = (size_t)U * kThreads;
   for (size_t base = (size_t)blockIdx.x * kPer; base < stride4; base += (size_t)gridDim.x * kPer) {
     size_t col[U];
@@ -118,12 +120,11 @@ __global__ __launch_bounds__(kThreads) void average_kernel(f32x4_t* __restrict__
 }
 
 // Node average into a separate vector (and its bf16 image): the replicas are only read.
-template <bool SHADOW, bool NT>
+template <bool SHADOW, bool NT, int U>
 __global__ __launch_bounds__(kThreads) void mean_kernel(const f32x4_t* __restrict__ params,
                                                         f32x4_t* __restrict__ out,
                                                         u32x2_t* __restrict__ out_shadow, size_t stride4,
                                                         int n, float n_f) {
-  constexpr int U = kColsPerThread;
   constexpr size_t kPer = (size_t)U * kThreads;
   for (size_t base = (size_t)blockIdx.x * kPer; base < stride4; base += (size_t)gridDim.x * kPer) {
     size_t col[U];
@@ -246,41 +247,106 @@ static int grid_for(size_t items, int max_blocks) {
 // 256 CUs x 8 resident workgroups: enough waves to cover HBM latency without a long tail.
 constexpr int kStreamBlocks = 256 * 8;
 
+// Small replica sets (fewer than a workgroup per compute unit at 256 columns each): a workgroup
+// takes 64 columns and its four wavefronts each sum a quarter of the replicas, so that four times
+// as many workgroups run and the chain of dependent loads per thread is four times shorter.  The
+// quarters are added in order through LDS; the broadcast form writes each quarter's replicas.
+template <bool SHADOW, bool BCAST>
+__global__ __launch_bounds__(kThreads) void restart_small_kernel(f32x4_t* __restrict__ params,
+                                                                 u32x2_t* __restrict__ shadow,
+                                                                 f32x4_t* __restrict__ out, size_t stride4,
+                                                                 int n, float n_f) {
+  __shared__ f32x4_t part[4][64];
+  const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const size_t c = (size_t)blockIdx.x * 64 + lane;
+  const bool ok = c < stride4;
+  const size_t col[1] = {ok ? c : 0};
+  const int n_per = (n + 3) / 4;
+  const int i0 = min(n, rg * n_per), i1 = min(n, i0 + n_per);
+  f32x4_t sum[1] = {(f32x4_t){0.0f, 0.0f, 0.0f, 0.0f}};
+  if (i1 > i0) replica_sums<false, 1>(params + (size_t)i0 * stride4, stride4, col, i1 - i0, sum);
+  part[rg][lane] = sum[0];
+  __syncthreads();
+  if (!ok) return;
+  const f32x4_t mean = (((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) / n_f;
+  if (BCAST) {
+    for (int i = i0; i < i1; ++i) params[(size_t)i * stride4 + c] = mean;
+    if (SHADOW) {
+      const u32x2_t h = pack_bf16x4(mean);
+      for (int i = i0; i < i1; ++i) shadow[(size_t)i * stride4 + c] = h;
+    }
+  } else if (rg == 0) {
+    out[c] = mean;
+    if (SHADOW) shadow[c] = pack_bf16x4(mean);
+  }
+}
+// Which decomposition a shape gets (the same for both restart kernels, so that they sum in the
+// same order and stay bit-identical to each other).
+static bool restart_is_small(size_t stride4, int n) { return n >= 8 && stride4 < (size_t)256 * 256; }
+
+template <bool SHADOW, bool NT, int U>
+static void launch_average_u(f32x4_t* p4, u32x2_t* s2, size_t stride4, int n, hipStream_t s) {
+  const int grid = grid_for((stride4 + U - 1) / U, 65536);
+  hipLaunchKernelGGL((average_kernel<SHADOW, NT, U>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n,
+                     (float)n);
+}
+template <bool SHADOW, bool NT, int U>
+static void launch_mean_u(const f32x4_t* p4, f32x4_t* o4, u32x2_t* s2, size_t stride4, int n, hipStream_t s) {
+  const int grid = grid_for((stride4 + U - 1) / U, 65536);
+  hipLaunchKernelGGL((mean_kernel<SHADOW, NT, U>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n,
+                     (float)n);
+}
+
 hipError_t launch_average(float* params, uint16_t* shadow, long m_pad, int n_workers, bool streaming,
                           hipStream_t s) {
   const size_t stride4 = (size_t)m_pad / 4;
-  // One column per thread in a single pass (measured best); the non-temporal variant is for
-  // replica sets far beyond the 256 MB last-level cache.
-  const bool nt = streaming;
-  const int grid = grid_for((stride4 + kColsPerThread - 1) / kColsPerThread, 65536);
+  // the non-temporal variants are for replica sets far beyond the 256 MB last-level cache
   f32x4_t* p4 = reinterpret_cast<f32x4_t*>(params);
   u32x2_t* s2 = reinterpret_cast<u32x2_t*>(shadow);
-  const float n_f = (float)n_workers;
-  if (shadow != nullptr) {
-    if (nt) hipLaunchKernelGGL((average_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
-    else hipLaunchKernelGGL((average_kernel<true, false>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
-  } else {
-    if (nt) hipLaunchKernelGGL((average_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
-    else hipLaunchKernelGGL((average_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, p4, s2, stride4, n_workers, n_f);
+  if (restart_is_small(stride4, n_workers)) {
+    const int grid = (int)((stride4 + 63) / 64);
+    if (shadow != nullptr)
+      hipLaunchKernelGGL((restart_small_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, p4, s2,
+                         (f32x4_t*)nullptr, stride4, n_workers, (float)n_workers);
+    else
+      hipLaunchKernelGGL((restart_small_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p4, s2,
+                         (f32x4_t*)nullptr, stride4, n_workers, (float)n_workers);
+    return hipGetLastError();
   }
+  const bool two = stride4 >= kTwoColumnsFrom;
+#define PRSGD_AVG(SH, NTV) \
+  do { if (two) launch_average_u<SH, NTV, 2>(p4, s2, stride4, n_workers, s); \
+       else launch_average_u<SH, NTV, 1>(p4, s2, stride4, n_workers, s); } while (0)
+  if (shadow != nullptr) { if (streaming) PRSGD_AVG(true, true); else PRSGD_AVG(true, false); }
+  else { if (streaming) PRSGD_AVG(false, true); else PRSGD_AVG(false, false); }
+#undef PRSGD_AVG
   return hipGetLastError();
 }
 
 hipError_t launch_mean(const float* params, float* out, uint16_t* out_shadow, long m_pad, int n_workers,
                        bool streaming, hipStream_t s) {
   const size_t stride4 = (size_t)m_pad / 4;
-  const int grid = grid_for((stride4 + kColsPerThread - 1) / kColsPerThread, 65536);
   const f32x4_t* p4 = reinterpret_cast<const f32x4_t*>(params);
   f32x4_t* o4 = reinterpret_cast<f32x4_t*>(out);
   u32x2_t* s2 = reinterpret_cast<u32x2_t*>(out_shadow);
-  const float n_f = (float)n_workers;
-  if (out_shadow != nullptr) {
-    if (streaming) hipLaunchKernelGGL((mean_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
-    else hipLaunchKernelGGL((mean_kernel<true, false>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
-  } else {
-    if (streaming) hipLaunchKernelGGL((mean_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
-    else hipLaunchKernelGGL((mean_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, p4, o4, s2, stride4, n_workers, n_f);
+  if (restart_is_small(stride4, n_workers)) {
+    const int grid = (int)((stride4 + 63) / 64);
+    f32x4_t* pm = const_cast<f32x4_t*>(p4);              // read only in this form
+    if (out_shadow != nullptr)
+      hipLaunchKernelGGL((restart_small_kernel<true, false>), dim3(grid), dim3(kThreads), 0, s, pm, s2, o4,
+                         stride4, n_workers, (float)n_workers);
+    else
+      hipLaunchKernelGGL((restart_small_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, pm, s2, o4,
+                         stride4, n_workers, (float)n_workers);
+    return hipGetLastError();
   }
+  const bool two = stride4 >= kTwoColumnsFrom;
+#define PRSGD_MEAN(SH, NTV) \
+  do { if (two) launch_mean_u<SH, NTV, 2>(p4, o4, s2, stride4, n_workers, s); \
+       else launch_mean_u<SH, NTV, 1>(p4, o4, s2, stride4, n_workers, s); } while (0)
+  if (out_shadow != nullptr) { if (streaming) PRSGD_MEAN(true, true); else PRSGD_MEAN(true, false); }
+  else { if (streaming) PRSGD_MEAN(false, true); else PRSGD_MEAN(false, false); }
+#undef PRSGD_MEAN
   return hipGetLastError();
 }
 

@@ -24,6 +24,8 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr unsigned kSpinLimit = 1u << 22;     // bounded wait: a lost team member aborts the launch
+constexpr int kTT = 512;                      // threads per team member: two wavefronts per SIMD, so
+constexpr int kTW = kTT / kWave;              // that the latency-bound phases of one overlap the other's
 constexpr int kAgentScope = 16;               // buffer-load cache policy: the sc1 bit (agent scope)
 
 __device__ __forceinline__ f32x4_t mfma16(float a, float b, f32x4_t c) {
@@ -39,7 +41,7 @@ __device__ __forceinline__ float act2_bwd(float h, int act) {
 // KBI: 16-row blocks of W_1 per wavefront (register budget); NT: 16-column tiles of the hidden
 // slice; MT: 16-row tiles of the minibatch.
 template <int KBI, int NT, int MT>
-__global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
+__global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   constexpr int W = NT * 16, MR = MT * 16;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
@@ -68,8 +70,8 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
 
   extern __shared__ __attribute__((aligned(16))) float lds[];
   float* X = lds;                                          // [MR][ldx]   gathered rows
-  float* red = X + (size_t)MR * ldx;                       // [4][MR][W]  per-wavefront partial z_1
-  float* h = red + 4 * MR * W;                             // [MR][W]
+  float* red = X + (size_t)MR * ldx;                       // [kTW][MR][W] per-wavefront partial z_1
+  float* h = red + kTW * MR * W;                           // [MR][W]
   float* dl1 = h + MR * W;                                 // [MR][W]
   float* lg = dl1 + MR * W;                                // [MR][D2P]   logits, then delta_2
   float* w2 = lg + MR * D2P;                               // [W][D2P]
@@ -89,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   float w1[KBI][NT][4];
 #pragma unroll
   for (int kbi = 0; kbi < KBI; ++kbi) {
-    const int kb = wave + 4 * kbi;
+    const int kb = wave + kTW * kbi;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -100,13 +102,13 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
         w1[kbi][nt][s] = ok ? v : 0.0f;
       }
   }
-  for (int e = tid; e < W * D2P; e += kThreads) {
+  for (int e = tid; e < W * D2P; e += kTT) {
     const int n = e / D2P, c = e % D2P;
     w2[e] = c < d2 ? prm0[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
   }
   if (tid < W) b1[tid] = prm0[p.b1_off + j * W + tid];
   if (tid < D2P) b2[tid] = tid < d2 ? prm0[p.b2_off + tid] : 0.0f;
-  for (int e = tid; e < MR * ldx; e += kThreads) X[e] = 0.0f;     // pad rows / columns stay zero
+  for (int e = tid; e < MR * ldx; e += kTT) X[e] = 0.0f;     // pad rows / columns stay zero
   if (tid == 0) flag[0] = 0;
   __syncthreads();
 
@@ -121,11 +123,11 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   // 16-byte column pc of rows rg, rg + ng, rg + 2 ng, ... (a row is at most 256 vectors wide).
   // Rows B .. MR-1 of X receive a copy of the first drawn row: finite values that only ever meet
   // zero deltas.
-  constexpr int PF = MT <= 2 ? 16 * MT : 0;                // vectors per thread; 0 = no prefetch
+  constexpr int PF = MT <= 2 ? 8 * MT : 0;                 // vectors per thread; 0 = no prefetch
   const int v4 = d0 >> 2, total4 = B * v4;
-  int cw_log = 4;                                          // ng <= 16 divides MR
+  int cw_log = 5;                                          // ng <= 16 divides MR
   while ((1 << cw_log) < v4) ++cw_log;
-  const int pc = tid & ((1 << cw_log) - 1), ng = kThreads >> cw_log;
+  const int pc = tid & ((1 << cw_log) - 1), ng = kTT >> cw_log;
   const bool pc_ok = pc < v4;
   int rg = tid >> cw_log;
   f32x4_t pre[PF > 0 ? PF : 1];
@@ -157,18 +159,18 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   // Gather without the register stage (shapes whose minibatch does not fit the register budget).
   auto gather_direct = [&]() {
     constexpr int G = 8;
-    for (int e0 = 0; e0 < total4; e0 += G * kThreads) {
+    for (int e0 = 0; e0 < total4; e0 += G * kTT) {
       f32x4_t v[G];
 #pragma unroll
       for (int u = 0; u < G; ++u) {
-        const int e = e0 + u * kThreads + tid;
+        const int e = e0 + u * kTT + tid;
         const int ec = e < total4 ? e : 0;
         const int r = ec / v4, c = ec - r * v4;
         v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
       }
 #pragma unroll
       for (int u = 0; u < G; ++u) {
-        const int e = e0 + u * kThreads + tid;
+        const int e = e0 + u * kTT + tid;
         if (e < total4) {
           const int r = e / v4, c = e - r * v4;
           *reinterpret_cast<f32x4_t*>(X + (size_t)r * ldx + 4 * c) = v[u];
@@ -185,21 +187,27 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   }
   __syncthreads();
   if constexpr (PF > 0) { gather_issue(rows); gather_store(); } else { gather_direct(); }
+  // rows and labels of the second iteration (the pipeline runs one iteration ahead)
+  int lab_next = 0;
+  if (PF > 0 && my_k > 1 && tid < B) {
+    const int r = sample_row(p.seed, (uint32_t)i, p.t0 + 2, (uint32_t)tid, p.log2n);
+    rows_next[tid] = r;
+    lab_next = lab[r];
+  }
   __syncthreads();
 
   // partial-logit exchange: Q 16-byte vectors per member; G groups of members are summed in
   // parallel (group g = members [g * PG, (g+1) * PG) in order), then the groups in order
   const int Q = MR * D2P / 4;
-  const int G = Q < kThreads ? kThreads / Q : 1;
+  const int G = Q < kTT ? kTT / Q : 1;
   const int PG = (p.P + G - 1) / G;
 
   for (int s = 1; s <= my_k; ++s) {
-    // (a) draw the rows of iteration s+1 (read back from LDS several barriers later)
-    int lab_next = 0;
-    if (PF > 0 && s < my_k && tid < B) {
-      const int r = sample_row(p.seed, (uint32_t)i, p.t0 + (uint64_t)s + 1, (uint32_t)tid, p.log2n);
-      rows_next[tid] = r;
-      lab_next = lab[r];
+    // (a) start the features of iteration s+1 (rows drawn one iteration ago) towards the
+    // registers: their issue stalls once the memory pipeline is full, and the matrix products
+    // of the forward slice below do not need that pipeline
+    if constexpr (PF > 0) {
+      if (s < my_k) gather_issue(rows_next);
     }
     // (c) forward slice: contraction index of MFMA step q is k = 16 kb + 4 q4 + q.  Row blocks
     // past the last one hold zero weights and re-read the last block, so the loop is branch-free.
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       // scheduling fence keeps the compiler from hoisting every block's reads (and their
       // registers) to the top
       auto load_a = [&](int kbi, f32x4_t (&a)[MT]) {
-        const int kb = min(wave + 4 * kbi, KB - 1);
+        const int kb = min(wave + kTW * kbi, KB - 1);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           a[mt] = *reinterpret_cast<const f32x4_t*>(X + (size_t)(mt * 16 + n16) * ldx + 16 * kb + 4 * q4);
@@ -242,21 +250,31 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
             red[((size_t)wave * MR + mt * 16 + 4 * q4 + v) * W + nt * 16 + n16] = acc[mt][nt][v];
     }
     __syncthreads();
-    for (int e = tid; e < MR * W; e += kThreads) {
+    for (int e = tid; e < MR * W; e += kTT) {
       const int b = e / W, n = e % W;
-      const float z = b1[n] + red[e] + red[MR * W + e] + red[2 * MR * W + e] + red[3 * MR * W + e];
+      float z = b1[n];
+#pragma unroll
+      for (int w = 0; w < kTW; ++w) z += red[w * MR * W + e];          // wavefronts in order
       h[e] = b < B ? act2_fwd(z, p.act) : 0.0f;
     }
     __syncthreads();
-    // (d) this slice's contribution to the logits
+    // (d) this slice's contribution to the logits, one 16 x 16 block per wavefront on the matrix
+    // cores: part[b][c] = sum_n h[b][n] W_2[n][c]  (rows b >= B of h are zero)
     float* my_part = p.part + (((size_t)(s & 1) * p.n_workers + i) * p.P + j) * part_team;
-    for (int e = tid; e < MR * D2P; e += kThreads) {
-      const int b = e / D2P, c = e % D2P;
-      float sum = 0.0f;
-#pragma unroll 8
-      for (int n = 0; n < W; ++n) sum = fmaf(h[b * W + n], w2[n * D2P + c], sum);
-      // agent-scope store: visible to the other compute units without flushing whole caches
-      __hip_atomic_store(my_part + e, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    {
+      const int ctiles = D2P >> 4;
+      for (int tile = wave; tile < MT * ctiles; tile += kTW) {
+        const int mt = tile / ctiles, ct = tile - mt * ctiles;
+        f32x4_t g = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int u = 0; u < NT * 4; ++u)
+          g = mfma16(h[(mt * 16 + n16) * W + 4 * u + q4], w2[(4 * u + q4) * D2P + ct * 16 + n16], g);
+        // agent-scope stores: visible to the other compute units without flushing whole caches
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          __hip_atomic_store(my_part + (mt * 16 + 4 * q4 + v) * D2P + ct * 16 + n16, g[v], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
     // (e) team barrier: arrivals are counted in HBM; the wait is bounded.  The partials were
     // written with agent-scope stores; draining this wavefront's stores before the workgroup
@@ -289,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       const __amdgpu_buffer_rsrc_t team_rsrc = __builtin_amdgcn_make_buffer_rsrc(
           const_cast<float*>(team_part), 0, (int)(p.P * part_team * sizeof(float)), 0x00020000);
       float* lgp = red;                                    // [G][MR * D2P] group sums
-      for (int w0 = tid; w0 < G * Q; w0 += kThreads) {     // one pass when Q <= 256
+      for (int w0 = tid; w0 < G * Q; w0 += kTT) {          // one pass when Q <= 512
         const int g = w0 / Q, q = w0 - g * Q;
         const int j_lo = g * PG, j_hi = min(p.P, j_lo + PG);
         f32x4_t sum = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
@@ -308,17 +326,13 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
         *reinterpret_cast<f32x4_t*>(lgp + (size_t)g * MR * D2P + 4 * q) = sum;
       }
     }
-    // the partials are in: start the next minibatch's features towards the registers
-    if constexpr (PF > 0) {
-      if (s < my_k) gather_issue(rows_next);
-    }
     __syncthreads();
     // logits = b_2 + group sums in order; softmax cross-entropy head, 16 lanes per minibatch
     // row, lane l holding classes l, l + 16, l + 32, l + 48 (d_2 <= 64)
     {
       const float* lgp = red;
       const int l16 = tid & 15;
-      for (int b = tid >> 4; b < MR; b += kThreads / 16) {
+      for (int b = tid >> 4; b < MR; b += kTT / 16) {
         float* row = lg + b * D2P;
         if (b < B) {
           float z[4];
@@ -364,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
     }
     __syncthreads();
     // (g) delta_1 slice (needs the pre-update W_2), then the small updates
-    for (int e = tid; e < MR * W; e += kThreads) {
+    for (int e = tid; e < MR * W; e += kTT) {
       const int b = e / W, n = e % W;
       float sum = 0.0f;
       for (int c = 0; c < D2P; c += 4) {
@@ -375,26 +389,39 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
       }
       dl1[e] = sum * act2_bwd(h[e], p.act);
     }
+    // dW_2 = h^T delta_2 (one 16 x 16 block per wavefront) and db_2 = column sums of delta_2 (a
+    // product with a matrix of ones) on the matrix cores, kept in registers until every read of
+    // the old W_2 above is done.  Rows b >= B of delta_2 are zero.
+    const int ctiles2 = D2P >> 4;
+    const bool has_w = wave < NT * ctiles2;                       // NT * ctiles2 <= 8 wavefronts
+    const int nt_w = wave / ctiles2, ct_w = wave - nt_w * ctiles2;
+    const int ct_b = kTW - 1 - wave;                              // db_2 blocks go to the last wavefronts
+    const bool has_b2 = ct_b < ctiles2;
+    f32x4_t gw = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f}, gb2 = gw;
+    if (has_w) {
+#pragma unroll
+      for (int u = 0; u < MT * 4; ++u)
+        gw = mfma16(h[(4 * u + q4) * W + nt_w * 16 + n16], lg[(4 * u + q4) * D2P + ct_w * 16 + n16], gw);
+    }
+    if (has_b2) {
+#pragma unroll
+      for (int u = 0; u < MT * 4; ++u) gb2 = mfma16(1.0f, lg[(4 * u + q4) * D2P + ct_b * 16 + n16], gb2);
+    }
     __syncthreads();
-    for (int e = tid; e < W * D2P; e += kThreads) {
-      const int n = e / D2P, c = e % D2P;
-      float sum = 0.0f;
-#pragma unroll 8
-      for (int b = 0; b < B; ++b) sum = fmaf(h[b * W + n], lg[b * D2P + c], sum);
-      w2[e] = fmaf(-p.lr, sum, w2[e]);
+    if (has_w) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        float* w = w2 + (nt_w * 16 + 4 * q4 + v) * D2P + ct_w * 16 + n16;
+        *w = fmaf(-p.lr, gw[v], *w);
+      }
     }
-    if (tid < D2P) {
-      float sum = 0.0f;
-#pragma unroll 8
-      for (int b = 0; b < B; ++b) sum += lg[b * D2P + tid];
-      b2[tid] = fmaf(-p.lr, sum, b2[tid]);
-    }
-    if (tid >= 64 && tid < 64 + W) {
-      const int n = tid - 64;
-      float sum = 0.0f;
-#pragma unroll 8
-      for (int b = 0; b < B; ++b) sum += dl1[b * W + n];
-      b1[n] = fmaf(-p.lr, sum, b1[n]);
+    if (has_b2 && q4 == 0) b2[ct_b * 16 + n16] = fmaf(-p.lr, gb2[0], b2[ct_b * 16 + n16]);
+    if (wave >= 2 && wave < 2 + NT) {                             // db_1 = column sums of delta_1
+      const int nt_b = wave - 2;
+      f32x4_t gb1 = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int u = 0; u < MT * 4; ++u) gb1 = mfma16(1.0f, dl1[(4 * u + q4) * W + nt_b * 16 + n16], gb1);
+      if (q4 == 0) b1[nt_b * 16 + n16] = fmaf(-p.lr, gb1[0], b1[nt_b * 16 + n16]);
     }
     // (h) dW_1 slice and eq. (3) in registers: contraction index of MFMA step u is b = 4u + q4
     {
@@ -404,7 +431,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) dfr[u][nt] = dl1[(4 * u + q4) * W + nt * 16 + n16];
       auto load_x = [&](int kbi, float (&a)[MT * 4]) {
-        const int kb = min(wave + 4 * kbi, KB - 1);
+        const int kb = min(wave + kTW * kbi, KB - 1);
 #pragma unroll
         for (int u = 0; u < MT * 4; ++u) a[u] = X[(size_t)(4 * u + q4) * ldx + 16 * kb + n16];
       };
@@ -420,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
         for (int u = 0; u < MT * 4; ++u)
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) g[nt] = mfma16(x_cur[u], dfr[u][nt], g[nt]);
-        const bool live = wave + 4 * kbi < KB;           // blocks past the end keep zero weights
+        const bool live = wave + kTW * kbi < KB;           // blocks past the end keep zero weights
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -436,7 +463,15 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
     if (s < my_k) {
       if constexpr (PF > 0) {
         gather_store();
-        if (tid < B) { rows[tid] = rows_next[tid]; ylab[tid] = lab_next; }
+        if (tid < B) {
+          rows[tid] = rows_next[tid];
+          ylab[tid] = lab_next;
+          if (s + 1 < my_k) {                            // rows and labels of iteration s+2
+            const int r = sample_row(p.seed, (uint32_t)i, p.t0 + (uint64_t)s + 2, (uint32_t)tid, p.log2n);
+            rows_next[tid] = r;
+            lab_next = lab[r];
+          }
+        }
       } else {
         if (tid < B) {
           const int r = sample_row(p.seed, (uint32_t)i, p.t0 + (uint64_t)s + 1, (uint32_t)tid, p.log2n);
@@ -454,7 +489,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
   // ---- write the slice back ------------------------------------------------------------------
 #pragma unroll
   for (int kbi = 0; kbi < KBI; ++kbi) {
-    const int kb = wave + 4 * kbi;
+    const int kb = wave + kTW * kbi;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -463,7 +498,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
         if (kb < KB && k < d0) prm[p.w1_off + (size_t)k * p.ld1 + j * W + nt * 16 + n16] = w1[kbi][nt][q];
       }
   }
-  for (int e = tid; e < W * D2P; e += kThreads) {
+  for (int e = tid; e < W * D2P; e += kTT) {
     const int n = e / D2P, c = e % D2P;
     if (c < d2) prm[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] = w2[e];
   }
@@ -478,7 +513,7 @@ __global__ __launch_bounds__(kThreads) void mlp2_epoch_kernel(Fused2Args p) {
 // ---- host side --------------------------------------------------------------------------------
 size_t fused2_lds_bytes(const Fused2Plan& pl) {
   const size_t MR = (size_t)pl.MT * 16, W = (size_t)pl.NT * 16;
-  const size_t floats = MR * pl.ldx + 4 * MR * W + 2 * MR * W + MR * pl.d2p + W * pl.d2p + W + pl.d2p +
+  const size_t floats = MR * pl.ldx + kTW * MR * W + 2 * MR * W + MR * pl.d2p + W * pl.d2p + W + pl.d2p +
                         3 * MR + 4;
   return floats * sizeof(float);
 }
@@ -489,10 +524,10 @@ template <int KBI, int NT, int MT> static const void* fused2_symbol() {
 
 static const void* fused2_pick(int kbi, int nt, int mt) {
 #define PICK(K, N, M) if (kbi == K && nt == N && mt == M) return fused2_symbol<K, N, M>();
+  PICK(2, 1, 1) PICK(2, 1, 2) PICK(2, 1, 4) PICK(2, 2, 1) PICK(2, 2, 2) PICK(2, 2, 4)
   PICK(4, 1, 1) PICK(4, 1, 2) PICK(4, 1, 4) PICK(4, 2, 1) PICK(4, 2, 2) PICK(4, 2, 4)
+  PICK(7, 1, 1) PICK(7, 1, 2) PICK(7, 1, 4) PICK(7, 2, 1) PICK(7, 2, 2) PICK(7, 2, 4)
   PICK(8, 1, 1) PICK(8, 1, 2) PICK(8, 1, 4) PICK(8, 2, 1) PICK(8, 2, 2) PICK(8, 2, 4)
-  PICK(13, 1, 1) PICK(13, 1, 2) PICK(13, 1, 4) PICK(13, 2, 1) PICK(13, 2, 2) PICK(13, 2, 4)
-  PICK(16, 1, 1) PICK(16, 1, 2) PICK(16, 1, 4) PICK(16, 2, 1) PICK(16, 2, 2) PICK(16, 2, 4)
 #undef PICK
   return nullptr;
 }
@@ -502,8 +537,8 @@ static const void* fused2_pick(int kbi, int nt, int mt) {
 bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* pl) {
   if (d0 < 4 || (d0 & 3) != 0 || d0 > 1024 || (d1 & 15) != 0 || d2 > 64 || batch > 64) return false;
   pl->MT = batch <= 16 ? 1 : batch <= 32 ? 2 : 4;
-  const int kb = (d0 + 15) / 16, kbi_need = (kb + 3) / 4;
-  pl->KBI = kbi_need <= 4 ? 4 : kbi_need <= 8 ? 8 : kbi_need <= 13 ? 13 : 16;
+  const int kb = (d0 + 15) / 16, kbi_need = (kb + kTW - 1) / kTW;
+  pl->KBI = kbi_need <= 2 ? 2 : kbi_need <= 4 ? 4 : kbi_need <= 7 ? 7 : 8;
   pl->d2p = (d2 + 15) / 16 * 16;
   int ldx = (d0 + 15) / 16 * 16 + 4;                        // (ldx / 4) odd: conflict-free 16-byte rows
   if (((ldx / 4) & 1) == 0) ldx += 4;
@@ -523,7 +558,7 @@ bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* p
     if (hipFuncSetAttribute(sym, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
       return false;
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sym, kThreads, lds_bytes) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sym, kTT, lds_bytes) != hipSuccess)
       return false;
     if ((long)n_workers * pl->P <= (long)per_cu * cus) return true;
   }
@@ -539,7 +574,7 @@ hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s) {
   void* kargs[] = {&args};
   // Plain launch: fused2_plan has checked that the whole grid fits on the device at once, and a
   // team member that never shows up ends in the kernel's bounded wait, not in a hang.
-  return hipLaunchKernel(sym, dim3((unsigned)(args.n_workers * pl.P)), dim3(kThreads), kargs,
+  return hipLaunchKernel(sym, dim3((unsigned)(args.n_workers * pl.P)), dim3(kTT), kargs,
                          fused2_lds_bytes(pl), s);
 }
 
