@@ -43,6 +43,8 @@ enum { PRSGD_OK = 0, PRSGD_EINVAL = -1, PRSGD_ESTATE = -2, PRSGD_EHIP = -3, PRSG
 enum { PRSGD_LSQ = 0, PRSGD_MLP = 1 };          /* objective F_i                          */
 enum { PRSGD_TANH = 0, PRSGD_RELU = 1 };        /* hidden activation of the MLP           */
 enum { PRSGD_F32 = 0, PRSGD_BF16 = 1 };         /* operand type of the matrix products    */
+/* what a restart does to the workers' momentum buffers (the paper does not say) */
+enum { PRSGD_MOM_KEEP = 0, PRSGD_MOM_AVERAGE = 1, PRSGD_MOM_RESET = 2 };
 #define PRSGD_MAX_DIMS 16
 
 /*
@@ -68,6 +70,13 @@ typedef struct {
   int64_t  rows_per_worker;        /* n, a power of two: rows in each worker's shard           */
   float    lr;                     /* gamma                                                    */
   uint64_t seed;                   /* seed of the minibatch index stream                       */
+  float    momentum;               /* mu in [0, 1).  0: the plain local step of eq. (3).  Otherwise the
+                                      momentum-SGD local step of the paper's experiment (Section 4,
+                                      momentum 0.9), in the form  v_i <- mu v_i + G_i,
+                                      x_i <- x_i - gamma v_i  with v_i = 0 at the start.  Runs on the
+                                      un-fused path (gradients in HBM + elementwise kernel).        */
+  int32_t  momentum_restart;       /* PRSGD_MOM_KEEP (buffers stay local, default) | _AVERAGE (node
+                                      average of the buffers overwrites them) | _RESET (zeroed)    */
 } prsgd_config;
 
 /* m: scalar parameters of one replica (0 if the config is invalid). */
@@ -105,6 +114,7 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k);
  * One epoch of the heterogeneous variant (Algorithm 3): worker i takes steps_host[i] >= 0
  * local iterations; a worker that has finished keeps its point (the paper's imagined
  * zero-gradient steps).  The iteration counter advances by max_i steps_host[i].
+ * Not defined with momentum (a zero-gradient step would still move the point): PRSGD_EINVAL.
  */
 int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host /* [N] */);
 
@@ -140,6 +150,12 @@ int prsgd_run(prsgd_ctx* ctx, int64_t iterations, int32_t interval);
 int prsgd_read_params(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m);
 /* Overwrites replica `worker`, or every replica with worker == -1 (checkpoint restore). */
 int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, size_t m);
+/*
+ * Momentum buffer v_i of worker `worker` (0..N-1) in the x0 layout, for checkpoints.
+ * PRSGD_ESTATE if the context was created with momentum == 0.  Synchronise the stream.
+ */
+int prsgd_read_velocity(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m);
+int prsgd_write_velocity(prsgd_ctx* ctx, int32_t worker, const float* in_host, size_t m);
 
 /* Minibatch loss F_i of each worker at its most recent local iteration, out_host[N]. */
 int prsgd_read_loss(prsgd_ctx* ctx, float* out_host);

@@ -13,6 +13,9 @@ Pins (tests/test_oracle_*.py, all run without a GPU):
                     eq. (5) mean recursion; eq. (6) restart identity; replicas
                     equal after every restart
   Algorithms 2, 3   reduce to Algorithm 1 for constant (gamma, K) / equal I_i
+  momentum          mu = 0 is Algorithm 1; geometric closed form under a constant gradient;
+                    N = 1 against an independently written heavy-ball loop; I = 1 with
+                    averaged buffers == momentum SGD on the averaged gradient; mean recursion
   bf16 rounding     torch's float32 -> bfloat16 conversion
 
 Parity unpinned: the long-horizon (thousands of non-convex steps) trajectory has
@@ -28,6 +31,7 @@ from .models import (  # noqa: F401
 )
 from .prsgd import (  # noqa: F401
     run_prsgd,
+    momentum_step,
     run_prsgd_literal,
     run_time_varying,
     run_heterogeneous,

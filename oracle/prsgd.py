@@ -60,13 +60,32 @@ def _start(x0, n_workers, x_init):
     return np.tile(np.asarray(x0, dtype=np.float64), (n_workers, 1))
 
 
+def momentum_step(x: np.ndarray, v: np.ndarray, g: np.ndarray, lr: float, mu: float) -> None:
+    """Momentum form of the local step, in place:  v <- mu v + G,  x <- x - gamma v.
+
+    The paper's experiment (Section 4) runs its local steps with momentum 0.9 in a framework
+    whose momentum SGD has exactly this form; Algorithm 1 itself is the case mu = 0."""
+    v *= mu
+    v += g
+    x -= lr * v
+
+
 def run_prsgd(model: str, dims: Sequence[int], activation: str, features: np.ndarray,
               targets: np.ndarray, x0: np.ndarray, n_workers: int, batch: int, lr: float,
               interval: int, iterations: int, seed: int, bf16: bool = False,
               t_start: int = 0, x_init: Optional[np.ndarray] = None,
-              record: Recorder = None) -> Dict:
-    """Algorithm 1 (restart form).  Returns {'x': [N][m], 'losses': [N], 't': int}."""
+              record: Recorder = None, momentum: float = 0.0, momentum_restart: str = "keep",
+              v_init: Optional[np.ndarray] = None) -> Dict:
+    """Algorithm 1 (restart form).  Returns {'x': [N][m], 'losses': [N], 't': int, 'v': [N][m]}.
+
+    With ``momentum`` > 0 every worker keeps a momentum buffer v_i (zero at the start) and takes
+    ``momentum_step`` instead of eq. (3).  The paper does not say what a restart does to the
+    buffers; ``momentum_restart`` selects "keep" (they stay local), "average" (their node average
+    overwrites them, like the points) or "reset" (zeroed)."""
+    if momentum_restart not in ("keep", "average", "reset"):
+        raise ValueError(momentum_restart)
     x = _start(x0, n_workers, x_init)
+    v = np.zeros_like(x) if v_init is None else np.array(v_init, dtype=np.float64, copy=True)
     losses = np.full(n_workers, np.nan)
     t = t_start
     for _ in range(iterations):
@@ -74,16 +93,23 @@ def run_prsgd(model: str, dims: Sequence[int], activation: str, features: np.nda
         g, losses, rows = _gradients(model, dims, activation, features, targets, x, t, batch,
                                      seed, bf16)
         x_before = x.copy() if record else None
-        x -= lr * g                                         # eq. (3)
+        if momentum != 0.0:
+            momentum_step(x, v, g, lr, momentum)
+        else:
+            x -= lr * g                                     # eq. (3)
         averaged = (t % interval == 0)
         x_stepped = x.copy() if record else None
         if averaged:                                        # restart from the node average
             x[:] = node_average(x)
+            if momentum != 0.0 and momentum_restart == "average":
+                v[:] = node_average(v)
+            elif momentum != 0.0 and momentum_restart == "reset":
+                v[:] = 0.0
         if record:
             record({"t": t, "g": g, "rows": rows, "x_before": x_before,
                     "x_stepped": x_stepped, "x_after": x.copy(), "averaged": averaged,
-                    "losses": losses.copy()})
-    return {"x": x, "losses": losses, "t": t}
+                    "losses": losses.copy(), "v": v.copy()})
+    return {"x": x, "losses": losses, "t": t, "v": v}
 
 
 def run_prsgd_literal(model: str, dims: Sequence[int], activation: str, features: np.ndarray,

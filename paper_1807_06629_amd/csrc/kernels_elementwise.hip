@@ -206,6 +206,44 @@ __global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ x,
   }
 }
 
+// Momentum form of the local step:  v <- mu v + g,  x <- x - lr v  (one rounding each).
+template <int U, bool NT>
+__global__ __launch_bounds__(kThreads) void momentum_update_kernel(f32x4_t* __restrict__ x4,
+                                                                   f32x4_t* __restrict__ v4,
+                                                                   const f32x4_t* __restrict__ g4,
+                                                                   u32x2_t* __restrict__ s4, size_t count4,
+                                                                   float lr, float mu) {
+  constexpr size_t kPer = (size_t)U * kThreads;
+  for (size_t b = (size_t)blockIdx.x * kPer; b < count4; b += (size_t)gridDim.x * kPer) {
+    f32x4_t xv[U], vv[U], gv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t k = b + (size_t)u * kThreads + threadIdx.x;
+      if (k < count4) { xv[u] = ld4<NT>(x4 + k); vv[u] = ld4<NT>(v4 + k); gv[u] = ld4<NT>(g4 + k); }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t k = b + (size_t)u * kThreads + threadIdx.x;
+      if (k < count4) {
+        f32x4_t v = vv[u], w = xv[u];
+        v.x = fmaf(mu, v.x, gv[u].x); v.y = fmaf(mu, v.y, gv[u].y);
+        v.z = fmaf(mu, v.z, gv[u].z); v.w = fmaf(mu, v.w, gv[u].w);
+        w.x = fmaf(-lr, v.x, w.x); w.y = fmaf(-lr, v.y, w.y);
+        w.z = fmaf(-lr, v.z, w.z); w.w = fmaf(-lr, v.w, w.w);
+        st4<NT>(v4 + k, v);
+        st4<NT>(x4 + k, w);
+        if (s4 != nullptr) st2<NT>(s4 + k, pack_bf16x4(w));
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(f32x4_t* __restrict__ x4, size_t count4) {
+  for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < count4;
+       k += (size_t)gridDim.x * kThreads)
+    x4[k] = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+}
+
 // Same update over [N][m_pad] with finished workers (Algorithm 3) left untouched.
 __global__ __launch_bounds__(kThreads) void update_masked_kernel(float4* __restrict__ x,
                                                                  const float4* __restrict__ g,
@@ -384,6 +422,31 @@ hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t coun
   const int grid = grid_for((count / 4 + U - 1) / U + 1, 65536);
   if (nt) hipLaunchKernelGGL((update_kernel<U, true>), dim3(grid), dim3(kThreads), 0, s, x, g, shadow, count, lr);
   else hipLaunchKernelGGL((update_kernel<U, false>), dim3(grid), dim3(kThreads), 0, s, x, g, shadow, count, lr);
+  return hipGetLastError();
+}
+
+// count is a multiple of 4 (whole padded replica buffers).
+hipError_t launch_momentum_update(float* x, float* v, const float* g, uint16_t* shadow, size_t count,
+                                  float lr, float mu, hipStream_t s) {
+  if (count == 0) return hipSuccess;
+  const bool nt = count * sizeof(float) >= ((size_t)1 << 28);
+  constexpr int U = 2;
+  const size_t count4 = count / 4;
+  const int grid = grid_for((count4 + U - 1) / U, 65536);
+  f32x4_t* x4 = reinterpret_cast<f32x4_t*>(x);
+  f32x4_t* v4 = reinterpret_cast<f32x4_t*>(v);
+  const f32x4_t* g4 = reinterpret_cast<const f32x4_t*>(g);
+  u32x2_t* s4 = reinterpret_cast<u32x2_t*>(shadow);
+  if (nt) hipLaunchKernelGGL((momentum_update_kernel<U, true>), dim3(grid), dim3(kThreads), 0, s, x4, v4, g4, s4, count4, lr, mu);
+  else hipLaunchKernelGGL((momentum_update_kernel<U, false>), dim3(grid), dim3(kThreads), 0, s, x4, v4, g4, s4, count4, lr, mu);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float* x, size_t count, hipStream_t s) {
+  const size_t count4 = count / 4;
+  if (count4 == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(count4, kStreamBlocks)), dim3(kThreads), 0, s,
+                     reinterpret_cast<f32x4_t*>(x), count4);
   return hipGetLastError();
 }
 

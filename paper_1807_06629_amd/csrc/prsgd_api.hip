@@ -30,7 +30,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local char g_init_error[256] = "";
 
 struct Carve {
-  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, mean_shadow = 0, steps = 0;
+  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, mean_shadow = 0, steps = 0, vel = 0;
   size_t h[PRSGD_MAX_DIMS] = {0}, delta[PRSGD_MAX_DIMS] = {0};
   size_t total = 0;
 };
@@ -44,6 +44,9 @@ bool build_layout(const prsgd_config* c, Layout* lo, char* err, size_t errn) {
       (c->rows_per_worker & (c->rows_per_worker - 1)) != 0)
     return fail("rows_per_worker must be a power of two");
   if (!(c->lr == c->lr)) return fail("lr is NaN");
+  if (!(c->momentum >= 0.0f && c->momentum < 1.0f)) return fail("momentum must be in [0, 1)");
+  if (c->momentum_restart < PRSGD_MOM_KEEP || c->momentum_restart > PRSGD_MOM_RESET)
+    return fail("unknown momentum_restart");
   memset(lo, 0, sizeof(*lo));
   if (c->model == PRSGD_LSQ) {
     if (c->n_dims != 1) return fail("least squares takes n_dims == 1");
@@ -78,7 +81,17 @@ bool build_layout(const prsgd_config* c, Layout* lo, char* err, size_t errn) {
   return true;
 }
 
-void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
+// Momentum runs on the un-fused path: the gradients go to HBM and an elementwise kernel applies
+// v <- mu v + G, x <- x - gamma v.
+prsgd_config effective_config(const prsgd_config* c) {
+  prsgd_config e = *c;
+  if (e.momentum != 0.0f) e.fused_update = 0;
+  return e;
+}
+
+void build_carve(const prsgd_config* c_in, const Layout& lo, Carve* cv) {
+  const prsgd_config eff = effective_config(c_in);
+  const prsgd_config* c = &eff;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kAlign); return o; };
   const size_t n = (size_t)c->n_workers, b = (size_t)c->batch;
@@ -88,6 +101,7 @@ void build_carve(const prsgd_config* c, const Layout& lo, Carve* cv) {
   cv->losses = take(n * 4);
   cv->steps = take(n * 4);
   cv->mean = take((size_t)lo.m_pad * 4);
+  if (c->momentum != 0.0f) cv->vel = take(n * (size_t)lo.m_pad * 4);
   if (c->model == PRSGD_MLP) {
     const int L = lo.n_layers;
     cv->yb = take(n * b * 4);
@@ -151,6 +165,7 @@ struct prsgd_ctx {
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   uint16_t* shadow() const { return bf16 ? at<uint16_t>(cv.shadow) : nullptr; }
   float* mean() const { return at<float>(cv.mean); }
+  float* velocity() const { return cfg.momentum != 0.0f ? at<float>(cv.vel) : nullptr; }
   uint16_t* mean_shadow() const { return bf16 ? at<uint16_t>(cv.mean_shadow) : nullptr; }
   // where a worker's current point is read from, and the stride between workers
   const float* src() const { return at_mean ? mean() : params; }
@@ -328,7 +343,10 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
   }
 
   if (!c.fused_update) {
-    if (worker_steps == nullptr)
+    if (ctx->velocity() != nullptr)
+      LAUNCH(ctx, KK_UPDATE, launch_momentum_update(ctx->params, ctx->velocity(), ctx->grads(), ctx->shadow(),
+                                                    (size_t)N * lo.m_pad, ctx->lr, c.momentum, s));
+    else if (worker_steps == nullptr)
       LAUNCH(ctx, KK_UPDATE, launch_update(ctx->params, ctx->grads(), ctx->shadow(),
                                            (size_t)N * lo.m_pad, ctx->lr, s));
     else
@@ -464,7 +482,7 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
 
   prsgd_ctx* ctx = new (std::nothrow) prsgd_ctx();
   if (ctx == nullptr) return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
-  ctx->cfg = *cfg;
+  ctx->cfg = effective_config(cfg);
   ctx->lo = lo;
   build_carve(cfg, lo, &ctx->cv);
   ctx->bf16 = cfg->model == PRSGD_MLP && cfg->gemm_dtype == PRSGD_BF16;
@@ -520,7 +538,7 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
     if (k == 0) return PRSGD_OK;
     LAUNCH(ctx, KK_LSQ,
            launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->src(),
-                            ctx->src_stride(), ctx->params,
+                            ctx->src_stride(), ctx->params, ctx->velocity(), c.momentum,
                             ctx->at<float>(ctx->cv.losses), ctx->at<int32_t>(ctx->cv.idx), c.n_workers,
                             ctx->lo.d[0], ctx->lo.m_pad, (long)c.rows_per_worker, c.batch, ctx->lr, c.seed,
                             ctx->t, k, nullptr, ctx->stream));
@@ -547,6 +565,8 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
 int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (steps_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "steps_host is null");
+  if (ctx->cfg.momentum != 0.0f)
+    return set_err(ctx, PRSGD_EINVAL, "heterogeneous epochs are not defined with momentum");
   const prsgd_config& c = ctx->cfg;
   int32_t k_max = 0;
   for (int i = 0; i < c.n_workers; ++i) {
@@ -565,7 +585,7 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
   if (c.model == PRSGD_LSQ) {
     LAUNCH(ctx, KK_LSQ,
            launch_lsq_steps(ctx->features, reinterpret_cast<const float*>(ctx->targets), ctx->params,
-                            ctx->lo.m_pad, ctx->params,
+                            ctx->lo.m_pad, ctx->params, nullptr, 0.0f,
                             ctx->at<float>(ctx->cv.losses), ctx->at<int32_t>(ctx->cv.idx), c.n_workers,
                             ctx->lo.d[0], ctx->lo.m_pad, (long)c.rows_per_worker, c.batch, ctx->lr, c.seed,
                             ctx->t, k_max, steps_dev, ctx->stream));
@@ -589,6 +609,16 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
 int prsgd_average(prsgd_ctx* ctx) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (ctx->at_mean) return PRSGD_OK;        // all workers already sit at their node average
+  if (ctx->velocity() != nullptr && ctx->cfg.momentum_restart != PRSGD_MOM_KEEP) {
+    // the paper leaves the momentum buffers at a restart open: average them like the points,
+    // or start every epoch without momentum
+    if (ctx->cfg.momentum_restart == PRSGD_MOM_AVERAGE)
+      LAUNCH(ctx, KK_AVERAGE, launch_average(ctx->velocity(), nullptr, ctx->lo.m_pad, ctx->cfg.n_workers,
+                                             ctx->streaming, ctx->stream));
+    else
+      LAUNCH(ctx, KK_UPDATE, launch_fill_zero(ctx->velocity(), (size_t)ctx->cfg.n_workers * ctx->lo.m_pad,
+                                              ctx->stream));
+  }
   if (ctx->lazy_restart && ctx->can_start_from_mean()) {
     // eq. (2) without the broadcast: ybar is written once; the next local iteration reads it as
     // every worker's starting point and writes the replicas  x_i = ybar - gamma G_i  itself
@@ -685,6 +715,34 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
   }
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_write_params");
+  return PRSGD_OK;
+}
+
+int prsgd_read_velocity(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
+  if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
+  if (worker < 0 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
+  if (ctx->velocity() == nullptr) return set_err(ctx, PRSGD_ESTATE, "the context has no momentum buffers");
+  hipError_t e = hipMemcpyAsync(ctx->host_pad.data(), ctx->velocity() + (size_t)worker * ctx->lo.m_pad,
+                                sizeof(float) * (size_t)ctx->lo.m_pad, hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_velocity");
+  dense_from_pad(ctx, ctx->host_pad.data(), out_host);
+  return PRSGD_OK;
+}
+
+int prsgd_write_velocity(prsgd_ctx* ctx, int32_t worker, const float* in_host, size_t m) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  if (in_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "in_host is null");
+  if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
+  if (worker < 0 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
+  if (ctx->velocity() == nullptr) return set_err(ctx, PRSGD_ESTATE, "the context has no momentum buffers");
+  pad_from_dense(ctx, in_host, ctx->host_pad.data());
+  hipError_t e = hipMemcpyAsync(ctx->velocity() + (size_t)worker * ctx->lo.m_pad, ctx->host_pad.data(),
+                                sizeof(float) * (size_t)ctx->lo.m_pad, hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_write_velocity");
   return PRSGD_OK;
 }
 

@@ -135,11 +135,14 @@ hipError_t launch_refresh_shadow(const float* params, uint16_t* shadow, long cou
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_update(float* x, const float* g, uint16_t* shadow, size_t count, float lr,
                          hipStream_t s);
+hipError_t launch_momentum_update(float* x, float* v, const float* g, uint16_t* shadow, size_t count,
+                                  float lr, float mu, hipStream_t s);
+hipError_t launch_fill_zero(float* x, size_t count, hipStream_t s);
 hipError_t launch_update_masked(float* x, const float* g, uint16_t* shadow, long m_pad, int n_workers,
                                 float lr, const int* worker_steps, int step, hipStream_t s);
 
 hipError_t launch_lsq_steps(const float* features, const float* targets, const float* src,
-                            long src_stride, float* params, float* losses,
+                            long src_stride, float* params, float* velocity, float mu, float* losses,
                             int32_t* idx, int n_workers, int d, long m_pad, long rows, int batch,
                             float lr, uint64_t seed, int64_t t0, int k, const int* worker_steps,
                             hipStream_t s);

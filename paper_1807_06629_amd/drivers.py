@@ -17,7 +17,8 @@ def open_workload(w, inputs: Dict[str, np.ndarray], device="cuda:0", fused_updat
     `w` is a hyper-parameter record with the fields of workloads.Workload."""
     cfg = prsgd.make_config(w.n_workers, w.model, w.dims, w.batch, w.rows_per_worker, w.lr,
                             w.index_seed, activation=w.activation, gemm_dtype=w.gemm_dtype,
-                            fused_update=fused_update)
+                            fused_update=fused_update, momentum=getattr(w, "momentum", 0.0),
+                            momentum_restart=getattr(w, "momentum_restart", "keep"))
     feats = torch.from_numpy(inputs["features"]).to(device)
     targs = torch.from_numpy(inputs["targets"]).to(device)
     return prsgd.prsgd_init(cfg, inputs["x0"], feats, targs, stream=stream)

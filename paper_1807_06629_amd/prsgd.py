@@ -22,6 +22,7 @@ PRSGD_OK, PRSGD_EINVAL, PRSGD_ESTATE, PRSGD_EHIP, PRSGD_ENOMEM = 0, -1, -2, -3, 
 PRSGD_LSQ, PRSGD_MLP = 0, 1
 PRSGD_TANH, PRSGD_RELU = 0, 1
 PRSGD_F32, PRSGD_BF16 = 0, 1
+PRSGD_MOM_KEEP, PRSGD_MOM_AVERAGE, PRSGD_MOM_RESET = 0, 1, 2
 PRSGD_MAX_DIMS = 16
 
 
@@ -44,6 +45,8 @@ class prsgd_config(ctypes.Structure):
         ("rows_per_worker", ctypes.c_int64),
         ("lr", ctypes.c_float),
         ("seed", ctypes.c_uint64),
+        ("momentum", ctypes.c_float),
+        ("momentum_restart", ctypes.c_int32),
     ]
 
 
@@ -70,6 +73,8 @@ def _load() -> ctypes.CDLL:
         "prsgd_run": (ctypes.c_int, [vp, i64, i32]),
         "prsgd_read_params": (ctypes.c_int, [vp, i32, vp, sz]),
         "prsgd_write_params": (ctypes.c_int, [vp, i32, vp, sz]),
+        "prsgd_read_velocity": (ctypes.c_int, [vp, i32, vp, sz]),
+        "prsgd_write_velocity": (ctypes.c_int, [vp, i32, vp, sz]),
         "prsgd_read_loss": (ctypes.c_int, [vp, vp]),
         "prsgd_read_indices": (ctypes.c_int, [vp, vp]),
         "prsgd_sample_indices": (ctypes.c_int, [ctypes.c_uint64, i32, i32, i64, i64, i32, vp, vp]),
@@ -95,7 +100,8 @@ _lib = _load()
 
 def make_config(n_workers: int, model: str, dims: Sequence[int], batch: int, rows_per_worker: int,
                 lr: float, seed: int, activation: str = "relu", gemm_dtype: str = "f32",
-                fused_update: bool = True) -> prsgd_config:
+                fused_update: bool = True, momentum: float = 0.0,
+                momentum_restart: str = "keep") -> prsgd_config:
     c = prsgd_config()
     c.n_workers = int(n_workers)
     c.model = {"lsq": PRSGD_LSQ, "mlp": PRSGD_MLP}[model]
@@ -111,6 +117,9 @@ def make_config(n_workers: int, model: str, dims: Sequence[int], batch: int, row
     c.rows_per_worker = int(rows_per_worker)
     c.lr = float(lr)
     c.seed = int(seed)
+    c.momentum = float(momentum)
+    c.momentum_restart = {"keep": PRSGD_MOM_KEEP, "average": PRSGD_MOM_AVERAGE,
+                          "reset": PRSGD_MOM_RESET}[momentum_restart]
     return c
 
 
@@ -218,6 +227,17 @@ def prsgd_read_params(h: Handle, worker: int) -> np.ndarray:
 def prsgd_write_params(h: Handle, worker: int, x: np.ndarray) -> None:
     x = np.ascontiguousarray(x, dtype=np.float32)
     _check(_lib.prsgd_write_params(h.ctx, int(worker), x.ctypes.data, x.size), h.ctx)
+
+
+def prsgd_read_velocity(h: Handle, worker: int) -> np.ndarray:
+    out = np.empty(h.m, dtype=np.float32)
+    _check(_lib.prsgd_read_velocity(h.ctx, int(worker), out.ctypes.data, out.size), h.ctx)
+    return out
+
+
+def prsgd_write_velocity(h: Handle, worker: int, v: np.ndarray) -> None:
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    _check(_lib.prsgd_write_velocity(h.ctx, int(worker), v.ctypes.data, v.size), h.ctx)
 
 
 def prsgd_read_loss(h: Handle) -> np.ndarray:

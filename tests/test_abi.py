@@ -63,6 +63,7 @@ def test_workspace_grows_with_shadow_and_gradient_buffers(P):
 @pytest.mark.parametrize("kw", [
     dict(n_workers=0), dict(batch=0), dict(batch=5000), dict(rows_per_worker=100),
     dict(rows_per_worker=0), dict(dims=(5,)), dict(dims=(0, 4)), dict(lr=float("nan")),
+    dict(momentum=1.0), dict(momentum=-0.1),
 ])
 def test_invalid_configurations_are_rejected_without_touching_the_gpu(P, kw):
     base = dict(n_workers=2, model="mlp", dims=(8, 4), batch=4, rows_per_worker=16, lr=0.1, seed=1)

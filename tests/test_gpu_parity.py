@@ -545,6 +545,75 @@ def test_algorithm3_heterogeneous_steps(P, D, model, fused):
     P.prsgd_destroy(h)
 
 
+# --------------------------------------------------------------------------- momentum local steps
+MOMENTUM_CASES = [
+    ("lsq", dict()),
+    ("one-hidden", dict(dims=(64, 32, 10), batch=8, n_workers=3)),          # the epoch kernel's shape
+    ("fp32-layers", dict(dims=(40, 24, 16, 6), batch=6, n_workers=3)),
+    ("bf16", dict(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="relu")),
+]
+
+
+@pytest.mark.parametrize("kind,kw", MOMENTUM_CASES)
+@pytest.mark.parametrize("mode", ["keep", "average", "reset"])
+def test_momentum_local_steps(P, D, kind, kw, mode):
+    if kind == "lsq":
+        w = get_workload("c1").scaled(rows_per_worker=128, n_workers=3, iterations=9, interval=2,
+                                      momentum=0.9, momentum_restart=mode)
+    else:
+        w = small_mlp(rows_per_worker=128, iterations=9, interval=2, lr=0.01, **kw)
+        w = w.scaled(momentum=0.9, momentum_restart=mode)
+    inp = make_inputs(w)
+    h = _open(D, w, inp)
+    names = _kernel_names(P, h, w.iterations, w.interval)
+    if kind != "lsq":                                   # momentum runs on the un-fused path
+        assert "sgd_update" in names and "mlp2_epoch" not in names and "gemm_bwd" not in names, names
+    want = oracle.run_prsgd(**oracle_args(w, inp), lr=w.lr, interval=w.interval, iterations=w.iterations,
+                            momentum=w.momentum, momentum_restart=mode)
+    got_x = D.read_all(h)
+    got_v = np.stack([P.prsgd_read_velocity(h, i) for i in range(w.n_workers)])
+    if kind == "bf16":
+        assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=BF16_LOSS_TOL)
+        assert rel_err(got_x, want["x"]) <= 2e-2
+    else:
+        assert rel_err(got_x, want["x"]) <= 1e-4
+        assert rel_err(got_v, want["v"]) <= 1e-4
+    P.prsgd_destroy(h)
+
+
+def test_momentum_checkpoint_resume_and_errors(P, D):
+    w = small_mlp(dims=(40, 24, 16, 6), batch=6, n_workers=3, iterations=14, interval=3)
+    w = w.scaled(momentum=0.9)
+    inp = inputs_for(w)
+    h = _open(D, w, inp)
+    P.prsgd_run(h, 14, 3)
+    full_x = D.read_all(h)
+    full_v = np.stack([P.prsgd_read_velocity(h, i) for i in range(w.n_workers)])
+    with pytest.raises(P.PrsgdError):                   # Algorithm 3 is not defined with momentum
+        P.prsgd_local_steps_hetero(h, [1, 1, 1])
+    P.prsgd_destroy(h)
+    h = _open(D, w, inp)
+    P.prsgd_run(h, 8, 3)
+    ck_x, t = D.read_all(h), P.prsgd_iteration(h)
+    ck_v = [P.prsgd_read_velocity(h, i) for i in range(w.n_workers)]
+    P.prsgd_destroy(h)
+    h = _open(D, w, inp)
+    for i in range(w.n_workers):
+        P.prsgd_write_params(h, i, ck_x[i])
+        P.prsgd_write_velocity(h, i, ck_v[i])
+    P.prsgd_set_iteration(h, t)
+    P.prsgd_run(h, 6, 3)
+    assert np.array_equal(D.read_all(h), full_x)
+    assert np.array_equal(np.stack([P.prsgd_read_velocity(h, i) for i in range(w.n_workers)]), full_v)
+    P.prsgd_destroy(h)
+    # no momentum buffers without momentum
+    w0 = small_mlp()
+    h = _open(D, w0, inputs_for(w0))
+    with pytest.raises(P.PrsgdError):
+        P.prsgd_read_velocity(h, 0)
+    P.prsgd_destroy(h)
+
+
 # --------------------------------------------------------------------------- stand-alone update
 @pytest.mark.parametrize("count", [4, 1000, 4099, 1 << 20])
 def test_standalone_sgd_update(P, count):

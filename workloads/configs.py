@@ -31,6 +31,8 @@ class Workload:
     data_seed: int = 1
     x0_seed: int = 2
     index_seed: int = 3
+    momentum: float = 0.0           # mu of the local momentum-SGD step (0: eq. 3 as printed)
+    momentum_restart: str = "keep"  # momentum buffers at a restart: "keep" | "average" | "reset"
 
     def scaled(self, **kw) -> "Workload":
         """A copy with some fields replaced (used for reduced-size test cases)."""
