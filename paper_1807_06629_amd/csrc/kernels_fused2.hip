@@ -44,7 +44,7 @@ template <int KBI, int NT, int MT>
 __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   constexpr int W = NT * 16, MR = MT * 16;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n16 = lane & 15, q4 = lane >> 4;
+  int n16 = lane & 15, q4 = lane >> 4;
 
   // team mapping: consecutive workgroups go round-robin to the 8 XCDs; keep a team on one XCD
   // (its partial logits then stay in that XCD's L2) when the worker count allows it
@@ -203,6 +203,9 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   const int PG = (p.P + G - 1) / G;
 
   for (int s = 1; s <= my_k; ++s) {
+    // opaque copies: LDS addresses built from the lane indices are recomputed every iteration
+    // instead of being hoisted out of the loop into dozens of (spilled) registers
+    asm volatile("" : "+v"(n16), "+v"(q4));
     // (a) start the features of iteration s+1 (rows drawn one iteration ago) towards the
     // registers: their issue stalls once the memory pipeline is full, and the matrix products
     // of the forward slice below do not need that pipeline
