@@ -204,8 +204,10 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
 
   for (int s = 1; s <= my_k; ++s) {
     // opaque copies: LDS addresses built from the lane indices are recomputed every iteration
-    // instead of being hoisted out of the loop into dozens of (spilled) registers
-    asm volatile("" : "+v"(n16), "+v"(q4));
+    // instead of being hoisted out of the loop into dozens of registers.  Measured: a gain for
+    // the shapes with few row blocks per wavefront; with many row blocks the matrix-instruction
+    // loops are issue-bound and run faster on hoisted addresses.
+    if constexpr (KBI <= 4) asm volatile("" : "+v"(n16), "+v"(q4));
     // (a) start the features of iteration s+1 (rows drawn one iteration ago) towards the
     // registers: their issue stalls once the memory pipeline is full, and the matrix products
     // of the forward slice below do not need that pipeline
