@@ -87,7 +87,10 @@ def test_c1_least_squares_full_run(P, D):
     P.prsgd_destroy(h)
 
 
-@pytest.mark.parametrize("d,batch", [(1, 1), (7, 3), (300, 70), (1000, 9)])
+# the shapes with d % 4 == 0 and at most 8192 minibatch floats take the LDS-staged kernel in each
+# of its four (vectors per thread, prefetch depth) variants; the others the plain kernel
+@pytest.mark.parametrize("d,batch", [(1, 1), (7, 3), (300, 70), (1000, 9), (4, 1), (32, 40), (128, 20),
+                                     (64, 100), (8, 300), (2048, 4), (16, 512)])
 def test_least_squares_ragged_shapes(P, D, d, batch):
     w = get_workload("c1").scaled(dims=(d,), batch=batch, rows_per_worker=128, n_workers=3,
                                   lr=0.01 / max(1, d // 64), interval=3, iterations=10)
