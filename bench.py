@@ -62,7 +62,8 @@ def algorithmic_work(w):
     dw_f = fwd_f
     # fused backward kernel (bf16 operands): master read + write, shadow write, the activation and
     # delta panels, and the delta of the layer below; both products
-    bwd_b = sum(n * (di * do * 10 + b * (di + do) * 2) for di, do in layers) + \
+    mom = 8 if getattr(w, "momentum", 0.0) != 0.0 else 0   # velocity read + write per element
+    bwd_b = sum(n * (di * do * (10 + mom) + b * (di + do) * 2) for di, do in layers) + \
         sum(n * b * di * 2 for di, do in layers[1:])
     out["gemm_bwd"] = {"bytes": bwd_b, "flops": dw_f + dx_f}
     out["gather"] = {"bytes": n * b * dims[0] * (4 + es), "flops": 0}
@@ -70,10 +71,10 @@ def algorithmic_work(w):
     out["gemm_dx"] = {"bytes": dx_b, "flops": dx_f}
     out["gemm_dw"] = {"bytes": dw_b, "flops": dw_f}
     out["softmax_xent"] = {"bytes": n * b * dims[-1] * (4 + es), "flops": 0}
-    out["sgd_update"] = {"bytes": n * m * (12 + shadow), "flops": 2 * n * m}
+    out["sgd_update"] = {"bytes": n * m * (12 + mom + shadow), "flops": (2 + (2 if mom else 0)) * n * m}
     # fused epoch kernel (one launch = `interval` iterations): per iteration the gathered rows and
     # all three products; the weights cross HBM once per launch (read + write), amortised here
-    out["mlp2_epoch"] = {"bytes": n * b * (dims[0] + 1) * 4 + 8.0 * n * m / max(1, w.interval),
+    out["mlp2_epoch"] = {"bytes": n * b * (dims[0] + 1) * 4 + (8.0 + mom) * n * m / max(1, w.interval),
                          "flops": fwd_f + dx_f + dw_f}
     out["average"] = {"bytes": n * m * 8 + n * pw * shadow, "flops": n * m}
     # restart with the broadcast deferred: every replica read once, the node average (and its
@@ -118,7 +119,8 @@ def cpu_baseline(w, inp, budget_s=20.0):
         cores = 1
     args = dict(model=w.model, dims=w.dims, activation=w.activation, features=inp["features"],
                 targets=inp["targets"], x0=inp["x0"], n_workers=w.n_workers, batch=w.batch,
-                lr=w.lr, interval=w.interval, seed=w.index_seed, bf16=(w.gemm_dtype == "bf16"))
+                lr=w.lr, interval=w.interval, seed=w.index_seed, bf16=(w.gemm_dtype == "bf16"),
+                momentum=w.momentum, momentum_restart=w.momentum_restart)
     t0 = time.perf_counter()
     oracle.run_prsgd(iterations=1, **args)
     t_one = time.perf_counter() - t0
@@ -198,6 +200,9 @@ def main() -> int:
     ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
     ap.add_argument("--eager-restart", action="store_true",
                     help="restart with the averaging kernel that overwrites every replica at once")
+    ap.add_argument("--momentum", type=float, default=None,
+                    help="momentum of the local steps (default: the workload's, 0 = eq. 3 as printed)")
+    ap.add_argument("--momentum-restart", choices=["keep", "average", "reset"], default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-average", action="store_true",
                     help="skip the extra HBM-scale timing of the averaging kernel")
@@ -244,6 +249,10 @@ def main() -> int:
         w = w.scaled(interval=args.interval)
     if args.rows is not None:
         w = w.scaled(rows_per_worker=args.rows)
+    if args.momentum is not None:
+        w = w.scaled(momentum=args.momentum)
+    if args.momentum_restart is not None:
+        w = w.scaled(momentum_restart=args.momentum_restart)
     steps = args.steps if args.steps is not None else min(w.iterations, 2000)
     warmup = args.warmup if args.warmup is not None else 2 * w.interval
 
@@ -327,6 +336,7 @@ def main() -> int:
             w.rows_per_worker, w.lr, w.activation),
             "n_workers": w.n_workers, "batch": w.batch, "interval": w.interval,
             "fused_update": not args.unfused, "deferred_broadcast": not args.eager_restart,
+            "momentum": w.momentum, "momentum_restart": w.momentum_restart,
             "last_minibatch_loss": loss},
         "roofline": roof,
         "restart_average": restart,

@@ -73,8 +73,11 @@ typedef struct {
   float    momentum;               /* mu in [0, 1).  0: the plain local step of eq. (3).  Otherwise the
                                       momentum-SGD local step of the paper's experiment (Section 4,
                                       momentum 0.9), in the form  v_i <- mu v_i + G_i,
-                                      x_i <- x_i - gamma v_i  with v_i = 0 at the start.  Runs on the
-                                      un-fused path (gradients in HBM + elementwise kernel).        */
+                                      x_i <- x_i - gamma v_i  with v_i = 0 at the start.  With
+                                      fused_update = 1 it is applied inside the one-pass backward
+                                      kernel (bf16 operands, B <= 128) or the epoch kernel (fp32,
+                                      one hidden layer); otherwise the gradients go to HBM and an
+                                      elementwise kernel applies it.                                */
   int32_t  momentum_restart;       /* PRSGD_MOM_KEEP (buffers stay local, default) | _AVERAGE (node
                                       average of the buffers overwrites them) | _RESET (zeroed)    */
 } prsgd_config;

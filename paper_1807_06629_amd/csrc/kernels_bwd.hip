@@ -66,8 +66,9 @@ __device__ __forceinline__ float dact_from_h(float h, int act) {
 }
 
 // MB: 32-row tiles of the minibatch held on chip (B <= 32 MB).  DX: also produce D_{l-1}.
-// S: weight tiles in flight per workgroup (register sets).
-template <int MB, bool DX, int S>
+// S: weight tiles in flight per workgroup (register sets).  MOM: momentum form of the local
+// update, v <- mu v + G, x <- x - gamma v, with the velocity tile streamed beside the weights.
+template <int MB, bool DX, int S, bool MOM>
 __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   constexpr int BR = 32 * MB;
   constexpr int NTD = DX ? (2 * MB + 3) / 4 : 1;     // D_{l-1} accumulator tiles per wavefront
@@ -101,6 +102,7 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   float* w_g = p.params + (size_t)g * p.p_gs + p.w_off;
   uint16_t* s_g = p.shadow + (size_t)g * p.p_gs + p.w_off;
   const float* wsrc_g = p.src + (size_t)g * p.src_gs + p.w_off;     // old weights
+  float* v_g = MOM ? p.vel + (size_t)g * p.p_gs + p.w_off : nullptr;   // velocity of W_l
   const bool nt = p.streaming != 0;
   const bool nt_read = nt && p.src_gs != 0;      // a shared source is re-read by every replica
 
@@ -138,6 +140,16 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
     }
     return mask;
   };
+  // the velocity tile in the same layout (private to the replica: always a streaming access)
+  auto fetch_v = [&](f32x4_t (&reg)[4], int n0, uint32_t mask) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int k = k0 + q * 16 + (tid >> 4), n = n0 + 4 * (tid & 15);
+      const bool ok = (mask >> q) & 1u;
+      const f32x4_t* src = reinterpret_cast<const f32x4_t*>(v_g + (ok ? (size_t)k * p.ldw + n : (size_t)0));
+      reg[q] = nt ? __builtin_nontemporal_load(src) : *src;
+    }
+  };
   auto stash_w = [&](const f32x4_t (&reg)[4], uint32_t mask) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -153,17 +165,22 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   const int n_t = (p.Nn + BN - 1) / BN;
   uint4 pr[MB];
   f32x4_t wr[S][4];
+  f32x4_t vr[MOM ? S : 1][4];
   uint32_t wm[S], dm;
   {
     const uint32_t hm = fetch_panel(pr, h_g, p.ldh, k0, p.K);
     wm[0] = fetch_w(wr[0], 0);
+    if (MOM) fetch_v(vr[0], 0, wm[0]);
     stash_panel(HT, SH, pr, hm);
   }
   dm = fetch_panel(pr, d_g, p.ldd, 0, p.Nn);
 #pragma unroll
   for (int st = 1; st < S; ++st) {
     wm[st] = 0;
-    if (st < n_t) wm[st] = fetch_w(wr[st], st * BN);
+    if (st < n_t) {
+      wm[st] = fetch_w(wr[st], st * BN);
+      if (MOM) fetch_v(vr[st], st * BN, wm[st]);
+    }
   }
 
   f32x16_t acc_dx[NTD];
@@ -177,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   // workgroup carries all of the bias work (the launch ends with its slowest workgroup)
 
   // one tile: (wr, wm) holds the weights of tile `it` and is refilled with tile it+S
-  auto tile_step = [&](int it, f32x4_t (&wr)[4], uint32_t& wm) {
+  auto tile_step = [&](int it, f32x4_t (&wr)[4], f32x4_t (&vr)[4], uint32_t& wm) {
     const int n0 = it * BN;
     stash_panel(Dl, SD, pr, dm);
     if (DX) stash_w(wr, wm);
@@ -225,7 +242,16 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
     for (int q = 0; q < 4; ++q) {
       if ((wm >> q) & 1u) {
         const int row = q * 16 + (tid >> 4), c = 4 * (tid & 15);
-        const f32x4_t gr = *reinterpret_cast<const f32x4_t*>(Gl + row * SG + c);
+        f32x4_t gr = *reinterpret_cast<const f32x4_t*>(Gl + row * SG + c);
+        const size_t off = (size_t)(k0 + row) * p.ldw + n0 + c;
+        if (MOM) {
+          gr.x = fmaf(p.mu, vr[q].x, gr.x);
+          gr.y = fmaf(p.mu, vr[q].y, gr.y);
+          gr.z = fmaf(p.mu, vr[q].z, gr.z);
+          gr.w = fmaf(p.mu, vr[q].w, gr.w);
+          if (nt) __builtin_nontemporal_store(gr, reinterpret_cast<f32x4_t*>(v_g + off));
+          else *reinterpret_cast<f32x4_t*>(v_g + off) = gr;
+        }
         f32x4_t w = wr[q];
         w.x = fmaf(-p.lr, gr.x, w.x);
         w.y = fmaf(-p.lr, gr.y, w.y);
@@ -234,7 +260,6 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
         uint2 hv;
         hv.x = (uint32_t)f32_to_bf16_rne(w.x) | ((uint32_t)f32_to_bf16_rne(w.y) << 16);
         hv.y = (uint32_t)f32_to_bf16_rne(w.z) | ((uint32_t)f32_to_bf16_rne(w.w) << 16);
-        const size_t off = (size_t)(k0 + row) * p.ldw + n0 + c;
         typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
         const u32x2_t hv2 = {hv.x, hv.y};
         if (nt) {
@@ -247,17 +272,25 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
       }
     }
     if (bias_turn && tid < BN && n0 + tid < p.Nn) {
-      const float cs = ((Bs[tid] + Bs[BN + tid]) + Bs[2 * BN + tid]) + Bs[3 * BN + tid];
+      float cs = ((Bs[tid] + Bs[BN + tid]) + Bs[2 * BN + tid]) + Bs[3 * BN + tid];
+      if (MOM) {
+        float* vb = p.vel + (size_t)g * p.p_gs + p.b_off + n0 + tid;
+        cs = fmaf(p.mu, *vb, cs);
+        *vb = cs;
+      }
       const float b_old = p.src[(size_t)g * p.src_gs + p.b_off + n0 + tid];
       p.params[(size_t)g * p.p_gs + p.b_off + n0 + tid] = fmaf(-p.lr, cs, b_old);
     }
-    if (it + S < n_t) wm = fetch_w(wr, n0 + S * BN);
+    if (it + S < n_t) {
+      wm = fetch_w(wr, n0 + S * BN);
+      if (MOM) fetch_v(vr, n0 + S * BN, wm);
+    }
   };
 
   for (int base = 0; base < n_t; base += S) {
 #pragma unroll
     for (int st = 0; st < S; ++st)
-      if (base + st < n_t) tile_step(base + st, wr[st], wm[st]);
+      if (base + st < n_t) tile_step(base + st, wr[st], vr[MOM ? st : 0], wm[st]);
   }
 
   // ---- D_{l-1} = acc * phi'(H_{l-1}) -------------------------------------------------------
@@ -282,13 +315,13 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   }
 }
 
-template <int MB, bool DX>
+template <int MB, bool DX, bool MOM>
 hipError_t launch_bwd_one(const BwdArgs& p, hipStream_t s) {
   constexpr int S = PRSGD_BWD_STAGES;
   constexpr int BR = 32 * MB;
   constexpr size_t kLds =
       sizeof(uint16_t) * (BR * SH + BR * SD + BMK * SW) + sizeof(float) * (BMK * SG + 4 * BN);
-  auto kernel = grouped_bwd_kernel<MB, DX, S>;
+  auto kernel = grouped_bwd_kernel<MB, DX, S, MOM>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -309,9 +342,14 @@ hipError_t launch_bwd_fused(const BwdArgs& p, hipStream_t s) {
   if (p.K <= 0 || p.Nn <= 0 || p.n_groups <= 0) return hipSuccess;
   if (!bwd_fused_supported(p.B)) return hipErrorInvalidValue;
   const bool dx = p.dx != nullptr;
-  if (p.B <= 32) return dx ? launch_bwd_one<1, true>(p, s) : launch_bwd_one<1, false>(p, s);
-  if (p.B <= 64) return dx ? launch_bwd_one<2, true>(p, s) : launch_bwd_one<2, false>(p, s);
-  return dx ? launch_bwd_one<4, true>(p, s) : launch_bwd_one<4, false>(p, s);
+  if (p.vel != nullptr) {
+    if (p.B <= 32) return dx ? launch_bwd_one<1, true, true>(p, s) : launch_bwd_one<1, false, true>(p, s);
+    if (p.B <= 64) return dx ? launch_bwd_one<2, true, true>(p, s) : launch_bwd_one<2, false, true>(p, s);
+    return dx ? launch_bwd_one<4, true, true>(p, s) : launch_bwd_one<4, false, true>(p, s);
+  }
+  if (p.B <= 32) return dx ? launch_bwd_one<1, true, false>(p, s) : launch_bwd_one<1, false, false>(p, s);
+  if (p.B <= 64) return dx ? launch_bwd_one<2, true, false>(p, s) : launch_bwd_one<2, false, false>(p, s);
+  return dx ? launch_bwd_one<4, true, false>(p, s) : launch_bwd_one<4, false, false>(p, s);
 }
 
 }  // namespace prsgd

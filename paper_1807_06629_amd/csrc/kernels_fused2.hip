@@ -39,8 +39,9 @@ __device__ __forceinline__ float act2_bwd(float h, int act) {
 }
 
 // KBI: 16-row blocks of W_1 per wavefront (register budget); NT: 16-column tiles of the hidden
-// slice; MT: 16-row tiles of the minibatch.
-template <int KBI, int NT, int MT>
+// slice; MT: 16-row tiles of the minibatch.  MOM: momentum form of the local update
+// (v <- mu v + G, x <- x - gamma v) with the velocity of the slice held next to the slice.
+template <int KBI, int NT, int MT, bool MOM>
 __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   constexpr int W = NT * 16, MR = MT * 16;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -80,7 +81,10 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   int* rows = reinterpret_cast<int*>(b2 + D2P);            // [MR] rows of this iteration
   int* ylab = rows + MR;                                   // [MR] their labels
   int* rows_next = ylab + MR;                              // [MR] rows of the next iteration
-  int* flag = rows_next + MR;                              // [1] abort broadcast
+  int* flag = rows_next + MR;                              // [4] abort broadcast
+  float* vw2 = reinterpret_cast<float*>(flag + 4);         // [W][D2P] velocities (MOM only)
+  float* vb1 = vw2 + W * D2P;                              // [W]
+  float* vb2 = vb1 + W;                                    // [D2P]
 
   float* prm = p.params + (size_t)i * p.m_pad;
   const float* prm0 = p.src + (size_t)i * p.src_stride;      // this worker's starting point
@@ -108,6 +112,30 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   }
   if (tid < W) b1[tid] = prm0[p.b1_off + j * W + tid];
   if (tid < D2P) b2[tid] = tid < d2 ? prm0[p.b2_off + tid] : 0.0f;
+  // velocity of the slice, same places
+  float* vel = MOM ? p.vel + (size_t)i * p.m_pad : nullptr;
+  float vw1[MOM ? KBI : 1][NT][4];
+  if constexpr (MOM) {
+#pragma unroll
+    for (int kbi = 0; kbi < KBI; ++kbi) {
+      const int kb = wave + kTW * kbi;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int k = 16 * kb + 4 * q4 + q;
+          const bool ok = kb < KB && k < d0;
+          const float v = vel[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
+          vw1[kbi][nt][q] = ok ? v : 0.0f;
+        }
+    }
+    for (int e = tid; e < W * D2P; e += kTT) {
+      const int n = e / D2P, c = e % D2P;
+      vw2[e] = c < d2 ? vel[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
+    }
+    if (tid < W) vb1[tid] = vel[p.b1_off + j * W + tid];
+    if (tid < D2P) vb2[tid] = tid < d2 ? vel[p.b2_off + tid] : 0.0f;
+  }
   for (int e = tid; e < MR * ldx; e += kTT) X[e] = 0.0f;     // pad rows / columns stay zero
   if (tid == 0) flag[0] = 0;
   __syncthreads();
@@ -123,7 +151,8 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   // 16-byte column pc of rows rg, rg + ng, rg + 2 ng, ... (a row is at most 256 vectors wide).
   // Rows B .. MR-1 of X receive a copy of the first drawn row: finite values that only ever meet
   // zero deltas.
-  constexpr int PF = MT <= 2 ? 8 * MT : 0;                 // vectors per thread; 0 = no prefetch
+  // vectors per thread; 0 = no prefetch (also where the velocity registers take its place)
+  constexpr int PF = (MT <= 2 && !(MOM && KBI * NT > 4)) ? 8 * MT : 0;
   const int v4 = d0 >> 2, total4 = B * v4;
   int cw_log = 5;                                          // ng <= 16 divides MR
   while ((1 << cw_log) < v4) ++cw_log;
@@ -416,17 +445,27 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     if (has_w) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        float* w = w2 + (nt_w * 16 + 4 * q4 + v) * D2P + ct_w * 16 + n16;
-        *w = fmaf(-p.lr, gw[v], *w);
+        const int e = (nt_w * 16 + 4 * q4 + v) * D2P + ct_w * 16 + n16;
+        float g = gw[v];
+        if constexpr (MOM) { g = fmaf(p.mu, vw2[e], g); vw2[e] = g; }
+        w2[e] = fmaf(-p.lr, g, w2[e]);
       }
     }
-    if (has_b2 && q4 == 0) b2[ct_b * 16 + n16] = fmaf(-p.lr, gb2[0], b2[ct_b * 16 + n16]);
+    if (has_b2 && q4 == 0) {
+      float g = gb2[0];
+      if constexpr (MOM) { g = fmaf(p.mu, vb2[ct_b * 16 + n16], g); vb2[ct_b * 16 + n16] = g; }
+      b2[ct_b * 16 + n16] = fmaf(-p.lr, g, b2[ct_b * 16 + n16]);
+    }
     if (wave >= 2 && wave < 2 + NT) {                             // db_1 = column sums of delta_1
       const int nt_b = wave - 2;
       f32x4_t gb1 = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int u = 0; u < MT * 4; ++u) gb1 = mfma16(1.0f, dl1[(4 * u + q4) * W + nt_b * 16 + n16], gb1);
-      if (q4 == 0) b1[nt_b * 16 + n16] = fmaf(-p.lr, gb1[0], b1[nt_b * 16 + n16]);
+      if (q4 == 0) {
+        float g = gb1[0];
+        if constexpr (MOM) { g = fmaf(p.mu, vb1[nt_b * 16 + n16], g); vb1[nt_b * 16 + n16] = g; }
+        b1[nt_b * 16 + n16] = fmaf(-p.lr, g, b1[nt_b * 16 + n16]);
+      }
     }
     // (h) dW_1 slice and eq. (3) in registers: contraction index of MFMA step u is b = 4u + q4
     {
@@ -456,8 +495,14 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            w1[kbi][nt][v] = live ? fmaf(-p.lr, g[nt][v], w1[kbi][nt][v]) : 0.0f;
+          for (int v = 0; v < 4; ++v) {
+            float gv = g[nt][v];
+            if constexpr (MOM) {
+              gv = live ? fmaf(p.mu, vw1[kbi][nt][v], gv) : 0.0f;
+              vw1[kbi][nt][v] = gv;
+            }
+            w1[kbi][nt][v] = live ? fmaf(-p.lr, gv, w1[kbi][nt][v]) : 0.0f;
+          }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < MT * 4; ++u) x_cur[u] = x_nxt[u];
@@ -508,6 +553,25 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     if (c < d2) prm[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] = w2[e];
   }
   if (tid < W) prm[p.b1_off + j * W + tid] = b1[tid];
+  if constexpr (MOM) {
+#pragma unroll
+    for (int kbi = 0; kbi < KBI; ++kbi) {
+      const int kb = wave + kTW * kbi;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int k = 16 * kb + 4 * q4 + q;
+          if (kb < KB && k < d0) vel[p.w1_off + (size_t)k * p.ld1 + j * W + nt * 16 + n16] = vw1[kbi][nt][q];
+        }
+    }
+    for (int e = tid; e < W * D2P; e += kTT) {
+      const int n = e / D2P, c = e % D2P;
+      if (c < d2) vel[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] = vw2[e];
+    }
+    if (tid < W) vel[p.b1_off + j * W + tid] = vb1[tid];
+    if (j == 0 && tid < d2) vel[p.b2_off + tid] = vb2[tid];
+  }
   if (j == 0) {
     if (tid < d2) prm[p.b2_off + tid] = b2[tid];
     if (tid < B) p.idx[(size_t)i * B + tid] = rows[tid];
@@ -518,17 +582,19 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
 // ---- host side --------------------------------------------------------------------------------
 size_t fused2_lds_bytes(const Fused2Plan& pl) {
   const size_t MR = (size_t)pl.MT * 16, W = (size_t)pl.NT * 16;
-  const size_t floats = MR * pl.ldx + kTW * MR * W + 2 * MR * W + MR * pl.d2p + W * pl.d2p + W + pl.d2p +
-                        3 * MR + 4;
+  size_t floats = MR * pl.ldx + kTW * MR * W + 2 * MR * W + MR * pl.d2p + W * pl.d2p + W + pl.d2p +
+                  3 * MR + 4;
+  if (pl.momentum) floats += W * pl.d2p + W + pl.d2p;
   return floats * sizeof(float);
 }
 
-template <int KBI, int NT, int MT> static const void* fused2_symbol() {
-  return reinterpret_cast<const void*>(mlp2_epoch_kernel<KBI, NT, MT>);
+template <int KBI, int NT, int MT> static const void* fused2_symbol(bool mom) {
+  return mom ? reinterpret_cast<const void*>(mlp2_epoch_kernel<KBI, NT, MT, true>)
+             : reinterpret_cast<const void*>(mlp2_epoch_kernel<KBI, NT, MT, false>);
 }
 
-static const void* fused2_pick(int kbi, int nt, int mt) {
-#define PICK(K, N, M) if (kbi == K && nt == N && mt == M) return fused2_symbol<K, N, M>();
+static const void* fused2_pick(int kbi, int nt, int mt, bool mom) {
+#define PICK(K, N, M) if (kbi == K && nt == N && mt == M) return fused2_symbol<K, N, M>(mom);
   PICK(2, 1, 1) PICK(2, 1, 2) PICK(2, 1, 4) PICK(2, 2, 1) PICK(2, 2, 2) PICK(2, 2, 4)
   PICK(4, 1, 1) PICK(4, 1, 2) PICK(4, 1, 4) PICK(4, 2, 1) PICK(4, 2, 2) PICK(4, 2, 4)
   PICK(7, 1, 1) PICK(7, 1, 2) PICK(7, 1, 4) PICK(7, 2, 1) PICK(7, 2, 2) PICK(7, 2, 4)
@@ -539,8 +605,9 @@ static const void* fused2_pick(int kbi, int nt, int mt) {
 
 // Decides whether the epoch kernel applies and how the team is shaped.  It needs every
 // workgroup of the grid resident at once (checked against the occupancy the runtime reports).
-bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* pl) {
+bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, bool momentum, Fused2Plan* pl) {
   if (d0 < 4 || (d0 & 3) != 0 || d0 > 1024 || (d1 & 15) != 0 || d2 > 64 || batch > 64) return false;
+  pl->momentum = momentum ? 1 : 0;
   pl->MT = batch <= 16 ? 1 : batch <= 32 ? 2 : 4;
   const int kb = (d0 + 15) / 16, kbi_need = (kb + kTW - 1) / kTW;
   pl->KBI = kbi_need <= 2 ? 2 : kbi_need <= 4 ? 4 : kbi_need <= 7 ? 7 : 8;
@@ -558,7 +625,7 @@ bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* p
     pl->P = d1 / (16 * nt);
     const size_t lds_bytes = fused2_lds_bytes(*pl);
     if (lds_bytes > 160 * 1024) continue;
-    const void* sym = fused2_pick(pl->KBI, pl->NT, pl->MT);
+    const void* sym = fused2_pick(pl->KBI, pl->NT, pl->MT, momentum);
     if (sym == nullptr) return false;
     if (hipFuncSetAttribute(sym, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
       return false;
@@ -571,8 +638,9 @@ bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* p
 }
 
 hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s) {
-  const void* sym = fused2_pick(pl.KBI, pl.NT, pl.MT);
+  const void* sym = fused2_pick(pl.KBI, pl.NT, pl.MT, pl.momentum != 0);
   if (sym == nullptr) return hipErrorInvalidValue;
+  if ((pl.momentum != 0) != (args.vel != nullptr)) return hipErrorInvalidValue;
   args.P = pl.P;
   args.d2p = pl.d2p;
   args.ldx = pl.ldx;

@@ -81,11 +81,21 @@ bool build_layout(const prsgd_config* c, Layout* lo, char* err, size_t errn) {
   return true;
 }
 
-// Momentum runs on the un-fused path: the gradients go to HBM and an elementwise kernel applies
-// v <- mu v + G, x <- x - gamma v.
+// Momentum (v <- mu v + G, x <- x - gamma v) is fused into the one-pass backward kernel of the
+// bf16 configurations and into the epoch kernel of the one-hidden-layer fp32 MLPs; elsewhere the
+// gradients go to HBM and an elementwise kernel applies it.
+bool bwd_fused_config(const prsgd_config& c) {
+  return c.model == PRSGD_MLP && c.gemm_dtype == PRSGD_BF16 && c.fused_update &&
+         prsgd::bwd_fused_supported(c.batch);
+}
+// shapes the epoch kernel may take (whether it does is decided at init, on the device)
+bool epoch_candidate(const prsgd_config& c) {
+  return c.model == PRSGD_MLP && c.gemm_dtype == PRSGD_F32 && c.n_dims == 3 && c.fused_update &&
+         (c.dims[1] % 16) == 0 && c.dims[2] <= 64 && c.batch <= 64;
+}
 prsgd_config effective_config(const prsgd_config* c) {
   prsgd_config e = *c;
-  if (e.momentum != 0.0f) e.fused_update = 0;
+  if (e.momentum != 0.0f && !bwd_fused_config(e) && !epoch_candidate(e)) e.fused_update = 0;
   return e;
 }
 
@@ -117,7 +127,7 @@ void build_carve(const prsgd_config* c_in, const Layout& lo, Carve* cv) {
       cv->shadow = take(n * (size_t)lo.m_pad * 2);
       cv->mean_shadow = take((size_t)lo.m_pad * 2);
     }
-    if (L == 2 && !bf16 && c->fused_update && (lo.d[1] % 16) == 0 && lo.d[2] <= 64 && c->batch <= 64) {
+    if (epoch_candidate(*c)) {
       // epoch kernel: partial logits for the finest team split, arrival counters, abort flag
       // batch tiles come in 1, 2 or 4 blocks of 16 rows
       const size_t mr = c->batch <= 16 ? 16 : c->batch <= 32 ? 32 : 64;
@@ -125,7 +135,9 @@ void build_carve(const prsgd_config* c_in, const Layout& lo, Carve* cv) {
       cv->part = take(2 * n * (size_t)(lo.d[1] / 16) * mr * d2p * 4);
       cv->sync = take((n + 1) * 128);
     }
-    if (!c->fused_update) cv->grads = take(n * (size_t)lo.m_pad * 4);
+    // un-fused update; also the fallback of a momentum run whose epoch kernel does not fit the device
+    if (!c->fused_update || (c->momentum != 0.0f && !bwd_fused_config(*c)))
+      cv->grads = take(n * (size_t)lo.m_pad * 4);
   }
   cv->total = off;
 }
@@ -315,6 +327,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
     q.B = B; q.K = lo.d[l - 1]; q.Nn = lo.d[l];
     q.n_groups = N; q.act = c.activation; q.streaming = ctx->streaming ? 1 : 0;
     q.lr = ctx->lr;
+    q.vel = ctx->velocity(); q.mu = c.momentum;
     q.worker_steps = worker_steps; q.step = step;
     LAUNCH(ctx, KK_BWD, launch_bwd_fused(q, s));
   }
@@ -386,6 +399,8 @@ Fused2Args fused2_args(prsgd_ctx* ctx, int k, const int* worker_steps) {
   a.sync = ctx->at<unsigned int>(ctx->cv.sync);
   a.row_loss = ctx->at<float>(ctx->cv.row_loss);
   a.idx = ctx->at<int32_t>(ctx->cv.idx);
+  a.vel = ctx->velocity();
+  a.mu = c.momentum;
   return a;
 }
 
@@ -489,7 +504,9 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   ctx->streaming = (size_t)cfg->n_workers * (size_t)lo.m_pad * sizeof(float) >= ((size_t)1 << 30);
   ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
   ctx->use_fused2 = ctx->cv.part != 0 && ctx->cv.sync != 0 &&
-                    fused2_plan(cfg->n_workers, lo.d[0], lo.d[1], lo.d[2], cfg->batch, &ctx->f2);
+                    fused2_plan(cfg->n_workers, lo.d[0], lo.d[1], lo.d[2], cfg->batch,
+                                cfg->momentum != 0.0f, &ctx->f2);
+  if (cfg->momentum != 0.0f && !bwd_fused_config(ctx->cfg) && !ctx->use_fused2) ctx->cfg.fused_update = 0;
   ctx->features = reinterpret_cast<const float*>(features_dev);
   ctx->targets = targets_dev;
   ctx->params = reinterpret_cast<float*>(params_dev);

@@ -80,6 +80,7 @@ struct BwdArgs {
   int B, K, Nn;                                 // minibatch rows, d_{l-1}, d_l
   int n_groups, act, streaming;
   float lr;
+  float* vel; float mu;                         // momentum buffers [N][p_gs] (nullptr = plain SGD)
   const int* worker_steps; int step;            // Algorithm 3 mask (nullptr = all active)
 };
 bool bwd_fused_supported(int batch);
@@ -90,6 +91,7 @@ struct Fused2Plan {
   int KBI, NT, MT;     // template shape: W_1 row blocks per wavefront, hidden tiles, batch tiles
   int P;               // workgroups per worker
   int d2p, ldx;        // padded class count, LDS row stride of the gathered batch
+  int momentum;        // 1: the variant that carries velocities
 };
 struct Fused2Args {
   const float* features; const int32_t* labels;
@@ -102,9 +104,10 @@ struct Fused2Args {
   float* part;                   // [2][N][P][MT*16][d2p] partial logits
   unsigned int* sync;            // [N][32] arrival counters (+ launch base), then the abort flag
   float* row_loss; int32_t* idx;
+  float* vel; float mu;          // momentum buffers [N][m_pad] (nullptr = plain SGD)
 };
 size_t fused2_lds_bytes(const Fused2Plan& pl);
-bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, Fused2Plan* pl);
+bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, bool momentum, Fused2Plan* pl);
 hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s);
 const char* kernel_kind_name(int kind);
 

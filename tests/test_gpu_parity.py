@@ -551,10 +551,18 @@ def test_algorithm3_heterogeneous_steps(P, D, model, fused):
 # --------------------------------------------------------------------------- momentum local steps
 MOMENTUM_CASES = [
     ("lsq", dict()),
-    ("one-hidden", dict(dims=(64, 32, 10), batch=8, n_workers=3)),          # the epoch kernel's shape
+    ("one-hidden", dict(dims=(64, 32, 10), batch=8, n_workers=3)),          # epoch kernel, prefetching variant
+    ("one-hidden-wide", dict(dims=(784, 64, 10), batch=32, n_workers=2, activation="tanh")),  # no prefetch
+    ("one-hidden-unfit", dict(dims=(64, 40, 10), batch=8, n_workers=3)),    # d_1 % 16 != 0: per-layer chain
     ("fp32-layers", dict(dims=(40, 24, 16, 6), batch=6, n_workers=3)),
     ("bf16", dict(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="relu")),
+    ("bf16-wide", dict(dims=(200, 136, 10), batch=100, n_workers=2, gemm_dtype="bf16", activation="relu")),
+    ("bf16-unfit", dict(dims=(60, 40, 10), batch=160, n_workers=2, gemm_dtype="bf16", activation="relu")),
 ]
+# which kernel applies the momentum update
+MOMENTUM_KERNEL = {"one-hidden": "mlp2_epoch", "one-hidden-wide": "mlp2_epoch", "one-hidden-unfit": "sgd_update",
+                   "fp32-layers": "sgd_update", "bf16": "gemm_bwd", "bf16-wide": "gemm_bwd",
+                   "bf16-unfit": "sgd_update"}
 
 
 @pytest.mark.parametrize("kind,kw", MOMENTUM_CASES)
@@ -569,19 +577,42 @@ def test_momentum_local_steps(P, D, kind, kw, mode):
     inp = make_inputs(w)
     h = _open(D, w, inp)
     names = _kernel_names(P, h, w.iterations, w.interval)
-    if kind != "lsq":                                   # momentum runs on the un-fused path
-        assert "sgd_update" in names and "mlp2_epoch" not in names and "gemm_bwd" not in names, names
+    if kind != "lsq":
+        others = {"sgd_update", "mlp2_epoch", "gemm_bwd"} - {MOMENTUM_KERNEL[kind]}
+        if mode == "reset":
+            others.discard("sgd_update")                # the velocity reset is booked under this label
+        assert MOMENTUM_KERNEL[kind] in names and not (others & set(names)), names
     want = oracle.run_prsgd(**oracle_args(w, inp), lr=w.lr, interval=w.interval, iterations=w.iterations,
                             momentum=w.momentum, momentum_restart=mode)
     got_x = D.read_all(h)
     got_v = np.stack([P.prsgd_read_velocity(h, i) for i in range(w.n_workers)])
-    if kind == "bf16":
+    if kind.startswith("bf16"):
         assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=BF16_LOSS_TOL)
         assert rel_err(got_x, want["x"]) <= 2e-2
+        assert rel_err(got_v, want["v"]) <= 2e-2
     else:
         assert rel_err(got_x, want["x"]) <= 1e-4
         assert rel_err(got_v, want["v"]) <= 1e-4
     P.prsgd_destroy(h)
+
+
+@pytest.mark.parametrize("kind,kw", [c for c in MOMENTUM_CASES if c[0] in ("lsq", "one-hidden", "bf16")])
+def test_momentum_deferred_broadcast_is_bit_identical(P, D, kind, kw):
+    if kind == "lsq":
+        w = get_workload("c1").scaled(rows_per_worker=128, n_workers=3, iterations=9, interval=2)
+    else:
+        w = small_mlp(rows_per_worker=128, iterations=9, interval=2, lr=0.01, **kw)
+    w = w.scaled(momentum=0.9, momentum_restart="average")
+    inp = make_inputs(w)
+    outs = []
+    for lazy in (True, False):
+        h = _open(D, w, inp)
+        P.prsgd_set_lazy_restart(h, lazy)
+        names = _kernel_names(P, h, w.iterations, w.interval)
+        assert ("restart_mean" in names) == lazy, names
+        outs.append((D.read_all(h), np.stack([P.prsgd_read_velocity(h, i) for i in range(w.n_workers)])))
+        P.prsgd_destroy(h)
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
 
 
 def test_momentum_checkpoint_resume_and_errors(P, D):
