@@ -25,6 +25,15 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr unsigned kSpinLimit = 1u << 22;     // bounded wait: a lost team member aborts the launch
 constexpr int kTT = 512;                      // threads per team member: two wavefronts per SIMD, so
+#ifndef PRSGD_F2_PF_WIDE
+#define PRSGD_F2_PF_WIDE 0         // prefetched vectors per thread and batch tile, shapes with many row blocks
+#endif
+#ifndef PRSGD_F2_DIRECT_G
+#define PRSGD_F2_DIRECT_G 8
+#endif
+#ifndef PRSGD_F2_PF_MOM
+#define PRSGD_F2_PF_MOM 0          // the same with momentum (velocity registers on top)
+#endif
 constexpr int kTW = kTT / kWave;              // that the latency-bound phases of one overlap the other's
 constexpr int kAgentScope = 16;               // buffer-load cache policy: the sc1 bit (agent scope)
 
@@ -80,8 +89,8 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   float* b2 = b1 + W;                                      // [D2P]
   int* rows = reinterpret_cast<int*>(b2 + D2P);            // [MR] rows of this iteration
   int* ylab = rows + MR;                                   // [MR] their labels
-  int* rows_next = ylab + MR;                              // [MR] rows of the next iteration
-  int* flag = rows_next + MR;                              // [4] abort broadcast
+  int* rows_ahead = ylab + MR;                             // [2][MR] rows of iteration t at [t & 1], drawn early
+  int* flag = rows_ahead + 2 * MR;                         // [4] abort broadcast
   float* vw2 = reinterpret_cast<float*>(flag + 4);         // [W][D2P] velocities (MOM only)
   float* vb1 = vw2 + W * D2P;                              // [W]
   float* vb2 = vb1 + W;                                    // [D2P]
@@ -151,8 +160,11 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   // 16-byte column pc of rows rg, rg + ng, rg + 2 ng, ... (a row is at most 256 vectors wide).
   // Rows B .. MR-1 of X receive a copy of the first drawn row: finite values that only ever meet
   // zero deltas.
-  // vectors per thread; 0 = no prefetch (also where the velocity registers take its place)
-  constexpr int PF = (MT <= 2 && !(MOM && KBI * NT > 4)) ? 8 * MT : 0;
+  // TV vectors per thread make up a minibatch; PF of them are requested an iteration early (0 = no
+  // prefetch): all of them where registers allow, otherwise half, and the rest at the end of the
+  // iteration through the same registers
+  constexpr int TV = 8 * MT;
+  constexpr int PF = MT > 2 ? 0 : (KBI * NT > 4) ? (MOM ? PRSGD_F2_PF_MOM : PRSGD_F2_PF_WIDE) * MT : TV;
   const int v4 = d0 >> 2, total4 = B * v4;
   int cw_log = 5;                                          // ng <= 16 divides MR
   while ((1 << cw_log) < v4) ++cw_log;
@@ -160,42 +172,53 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   const bool pc_ok = pc < v4;
   int rg = tid >> cw_log;
   f32x4_t pre[PF > 0 ? PF : 1];
-  auto gather_issue = [&](const int* rws) {
+  auto gather_issue = [&](const int* rws, int ub) {         // vectors ub .. ub + PF - 1
     // opaque copy: keeps the per-vector addresses and predicates from being hoisted out of the
     // iteration loop into (spilled) registers
     asm volatile("" : "+v"(rg));
     const float* src = feat + (pc_ok ? 4 * pc : 0);
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
-      if (ng * u < B) {                                    // uniform over the workgroup
-        const int r = rg + ng * u;
+      if (ng * (ub + u) < B) {                             // uniform over the workgroup
+        const int r = rg + ng * (ub + u);
         pre[u] = *reinterpret_cast<const f32x4_t*>(src + (size_t)rws[r < B ? r : 0] * d0);
       }
     }
   };
-  auto gather_store = [&]() {
+  auto gather_store = [&](int ub) {
     asm volatile("" : "+v"(rg));
     if (pc_ok) {
-      float* dst = X + (size_t)rg * ldx + 4 * pc;
+      float* dst = X + (size_t)(rg + ng * ub) * ldx + 4 * pc;
       const int step = ng * ldx;
 #pragma unroll
       for (int u = 0; u < PF; ++u) {
-        if (ng * u < B) *reinterpret_cast<f32x4_t*>(dst) = pre[u];
+        if (ng * (ub + u) < B) *reinterpret_cast<f32x4_t*>(dst) = pre[u];
         dst += step;
+      }
+    }
+  };
+  // the part of a minibatch that was not requested early
+  auto gather_rest = [&](const int* rws) {
+    if constexpr (PF > 0) {
+      for (int ub = PF; ub < TV; ub += PF) {
+        gather_issue(rws, ub);
+        gather_store(ub);
       }
     }
   };
   // Gather without the register stage (shapes whose minibatch does not fit the register budget).
   auto gather_direct = [&]() {
-    constexpr int G = 8;
+    constexpr int G = PRSGD_F2_DIRECT_G;                   // vectors in flight per thread
     for (int e0 = 0; e0 < total4; e0 += G * kTT) {
       f32x4_t v[G];
 #pragma unroll
       for (int u = 0; u < G; ++u) {
-        const int e = e0 + u * kTT + tid;
-        const int ec = e < total4 ? e : 0;
-        const int r = ec / v4, c = ec - r * v4;
-        v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
+        if (e0 + u * kTT < total4) {                       // uniform over the workgroup
+          const int e = e0 + u * kTT + tid;
+          const int ec = e < total4 ? e : 0;
+          const int r = ec / v4, c = ec - r * v4;
+          v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
+        }
       }
 #pragma unroll
       for (int u = 0; u < G; ++u) {
@@ -215,12 +238,12 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     ylab[tid] = lab[r];
   }
   __syncthreads();
-  if constexpr (PF > 0) { gather_issue(rows); gather_store(); } else { gather_direct(); }
+  if constexpr (PF > 0) { gather_issue(rows, 0); gather_store(0); gather_rest(rows); } else { gather_direct(); }
   // rows and labels of the second iteration (the pipeline runs one iteration ahead)
   int lab_next = 0;
   if (PF > 0 && my_k > 1 && tid < B) {
     const int r = sample_row(p.seed, (uint32_t)i, p.t0 + 2, (uint32_t)tid, p.log2n);
-    rows_next[tid] = r;
+    rows_ahead[tid] = r;                                   // iteration 2 of this call: slot 0
     lab_next = lab[r];
   }
   __syncthreads();
@@ -241,7 +264,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     // registers: their issue stalls once the memory pipeline is full, and the matrix products
     // of the forward slice below do not need that pipeline
     if constexpr (PF > 0) {
-      if (s < my_k) gather_issue(rows_next);
+      if (s < my_k) gather_issue(rows_ahead + ((s + 1) & 1) * MR, 0);
     }
     // (c) forward slice: contraction index of MFMA step q is k = 16 kb + 4 q4 + q.  Row blocks
     // past the last one hold zero weights and re-read the last block, so the loop is branch-free.
@@ -512,13 +535,15 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     // (i) the next minibatch takes its place
     if (s < my_k) {
       if constexpr (PF > 0) {
-        gather_store();
+        const int* rows_next = rows_ahead + ((s + 1) & 1) * MR;
+        gather_store(0);
+        gather_rest(rows_next);
         if (tid < B) {
           rows[tid] = rows_next[tid];
           ylab[tid] = lab_next;
-          if (s + 1 < my_k) {                            // rows and labels of iteration s+2
+          if (s + 1 < my_k) {                            // rows and labels of iteration s+2 (other slot)
             const int r = sample_row(p.seed, (uint32_t)i, p.t0 + (uint64_t)s + 2, (uint32_t)tid, p.log2n);
-            rows_next[tid] = r;
+            rows_ahead[(s & 1) * MR + tid] = r;
             lab_next = lab[r];
           }
         }
@@ -583,7 +608,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
 size_t fused2_lds_bytes(const Fused2Plan& pl) {
   const size_t MR = (size_t)pl.MT * 16, W = (size_t)pl.NT * 16;
   size_t floats = MR * pl.ldx + kTW * MR * W + 2 * MR * W + MR * pl.d2p + W * pl.d2p + W + pl.d2p +
-                  3 * MR + 4;
+                  4 * MR + 4;
   if (pl.momentum) floats += W * pl.d2p + W + pl.d2p;
   return floats * sizeof(float);
 }
