@@ -47,6 +47,24 @@ __device__ __forceinline__ float act2_bwd(float h, int act) {
   return act == PRSGD_TANH ? (1.0f - h * h) : (h > 0.0f ? 1.0f : 0.0f);
 }
 
+// Butterfly over each aligned group of 16 lanes on the data-parallel-primitive path (no LDS round
+// trips): every lane of the group ends with the same max / sum.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_move<0xB1>(v));      // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_move<0x4E>(v));      // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_move<0x141>(v));     // row_half_mirror
+  return fmaxf(v, dpp_move<0x140>(v));  // row_mirror
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  return v + dpp_move<0x140>(v);
+}
+
 // KBI: 16-row blocks of W_1 per wavefront (register budget); NT: 16-column tiles of the hidden
 // slice; MT: 16-row tiles of the minibatch.  MOM: momentum form of the local update
 // (v <- mu v + G, x <- x - gamma v) with the velocity of the slice held next to the slice.
@@ -206,29 +224,23 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
       }
     }
   };
-  // Gather without the register stage (shapes whose minibatch does not fit the register budget).
+  // Gather without the register stage (shapes whose minibatch does not fit the register budget):
+  // loads that write LDS directly, one instruction per 64 consecutive 16-byte vectors of a row
+  // (the lanes' data lands at consecutive LDS addresses from a wavefront-uniform base), so the
+  // whole minibatch is in flight at once at no register cost.
   auto gather_direct = [&]() {
-    constexpr int G = PRSGD_F2_DIRECT_G;                   // vectors in flight per thread
-    for (int e0 = 0; e0 < total4; e0 += G * kTT) {
-      f32x4_t v[G];
-#pragma unroll
-      for (int u = 0; u < G; ++u) {
-        if (e0 + u * kTT < total4) {                       // uniform over the workgroup
-          const int e = e0 + u * kTT + tid;
-          const int ec = e < total4 ? e : 0;
-          const int r = ec / v4, c = ec - r * v4;
-          v[u] = *reinterpret_cast<const f32x4_t*>(feat + (size_t)rows[r] * d0 + 4 * c);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < G; ++u) {
-        const int e = e0 + u * kTT + tid;
-        if (e < total4) {
-          const int r = e / v4, c = e - r * v4;
-          *reinterpret_cast<f32x4_t*>(X + (size_t)r * ldx + 4 * c) = v[u];
-        }
-      }
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int cpr = (v4 + 63) >> 6;                        // 64-vector chunks per row
+    for (int t = wave; t < B * cpr; t += kTW) {
+      const int r = t / cpr, ch = t - r * cpr;
+      const int c = 64 * ch + lane;
+      const int lds_off = __builtin_amdgcn_readfirstlane(r * ldx + 256 * ch);
+      if (c < v4)
+        __builtin_amdgcn_global_load_lds((gptr_t)(feat + (size_t)rows[r] * d0 + 4 * c), (lptr_t)(X + lds_off),
+                                         16, 0, 0);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the data is in LDS before the next barrier
   };
 
   // rows, labels and features of the first iteration
@@ -405,8 +417,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
               mx = fmaxf(mx, sum);
             }
           }
-#pragma unroll
-          for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 16));
+          mx = row16_max(mx);
           float ex[4];
           float se = 0.0f;
 #pragma unroll
@@ -414,8 +425,8 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
             ex[q] = (l16 + 16 * q < d2) ? expf(z[q] - mx) : 0.0f;
             se += ex[q];
           }
-#pragma unroll
-          for (int o = 8; o > 0; o >>= 1) se += __shfl_xor(se, o, 16);
+          se = row16_sum(se);
+          const float inv_se = __builtin_amdgcn_rcpf(se);    // 1 <= se <= 64; one ulp
           const int y = ylab[b];
           const bool y_ok = y >= 0 && y < d2;               // an out-of-range label selects nothing
           if (j == 0 && l16 == (y_ok ? (y & 15) : 0)) {
@@ -426,7 +437,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int c = l16 + 16 * q;
-            if (c < D2P) row[c] = c < d2 ? (ex[q] / se - (c == y ? 1.0f : 0.0f)) * inv_b : 0.0f;
+            if (c < D2P) row[c] = c < d2 ? (ex[q] * inv_se - (c == y ? 1.0f : 0.0f)) * inv_b : 0.0f;
           }
         } else {
           for (int c = l16; c < D2P; c += 16) row[c] = 0.0f;
