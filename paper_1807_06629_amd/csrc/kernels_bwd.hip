@@ -163,23 +163,28 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
 
   // ---- prologue -----------------------------------------------------------------------------
   const int n_t = (p.Nn + BN - 1) / BN;
+  // Every workgroup walks all column tiles, each from a different start: workgroups that run in
+  // step would otherwise all sit on the same byte offset inside their (power-of-two strided)
+  // weight rows, i.e. on the same few memory channels.
+  const int rot = (int)(((long)tile * n_t) / tiles + g) % n_t;
+  auto col_tile = [&](int i) { const int c = i + rot; return c >= n_t ? c - n_t : c; };
   uint4 pr[MB];
   f32x4_t wr[S][4];
   f32x4_t vr[MOM ? S : 1][4];
   uint32_t wm[S], dm;
   {
     const uint32_t hm = fetch_panel(pr, h_g, p.ldh, k0, p.K);
-    wm[0] = fetch_w(wr[0], 0);
-    if (MOM) fetch_v(vr[0], 0, wm[0]);
+    wm[0] = fetch_w(wr[0], col_tile(0) * BN);
+    if (MOM) fetch_v(vr[0], col_tile(0) * BN, wm[0]);
     stash_panel(HT, SH, pr, hm);
   }
-  dm = fetch_panel(pr, d_g, p.ldd, 0, p.Nn);
+  dm = fetch_panel(pr, d_g, p.ldd, col_tile(0) * BN, p.Nn);
 #pragma unroll
   for (int st = 1; st < S; ++st) {
     wm[st] = 0;
     if (st < n_t) {
-      wm[st] = fetch_w(wr[st], st * BN);
-      if (MOM) fetch_v(vr[st], st * BN, wm[st]);
+      wm[st] = fetch_w(wr[st], col_tile(st) * BN);
+      if (MOM) fetch_v(vr[st], col_tile(st) * BN, wm[st]);
     }
   }
 
@@ -195,11 +200,11 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
 
   // one tile: (wr, wm) holds the weights of tile `it` and is refilled with tile it+S
   auto tile_step = [&](int it, f32x4_t (&wr)[4], f32x4_t (&vr)[4], uint32_t& wm) {
-    const int n0 = it * BN;
+    const int ct = col_tile(it), n0 = ct * BN;
     stash_panel(Dl, SD, pr, dm);
     if (DX) stash_w(wr, wm);
     __syncthreads();
-    if (it + 1 < n_t) dm = fetch_panel(pr, d_g, p.ldd, n0 + BN, p.Nn);
+    if (it + 1 < n_t) dm = fetch_panel(pr, d_g, p.ldd, col_tile(it + 1) * BN, p.Nn);
 
     // dW tile block (wk, wn): contraction over the minibatch
     f32x16_t acc;
@@ -224,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
     }
     // db: column sums of the (rounded) delta tile; rows beyond B are zero.  Each wavefront sums
     // a quarter of the rows, the four partial sums are added in order after the barrier.
-    const bool bias_turn = (it % tiles) == tile;
+    const bool bias_turn = (ct % tiles) == tile;
     if (bias_turn) {
       float cs = 0.0f;
 #pragma unroll 8
@@ -282,8 +287,8 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
       p.params[(size_t)g * p.p_gs + p.b_off + n0 + tid] = fmaf(-p.lr, cs, b_old);
     }
     if (it + S < n_t) {
-      wm = fetch_w(wr, n0 + S * BN);
-      if (MOM) fetch_v(vr, n0 + S * BN, wm);
+      wm = fetch_w(wr, col_tile(it + S) * BN);
+      if (MOM) fetch_v(vr, col_tile(it + S) * BN, wm);
     }
   };
 
