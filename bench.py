@@ -32,7 +32,7 @@ KERNEL_SYMBOL = {
     "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>", "gemm_bwd": "grouped_bwd_kernel",
     "softmax_xent": "softmax_xent_kernel",
     "sgd_update": "update_kernel", "average": "average_kernel", "restart_mean": "mean_kernel",
-    "lsq_steps": "lsq_steps_kernel",
+    "lsq_steps": "lsq_steps_staged_kernel (lsq_steps_kernel for shapes it does not take)",
     "mlp2_epoch": "mlp2_epoch_kernel",
 }
 

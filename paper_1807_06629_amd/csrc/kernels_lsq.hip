@@ -184,7 +184,8 @@ __global__ __launch_bounds__(kThreads) void lsq_steps_staged_kernel(
   draw_block(1);
   __syncthreads();
 #pragma unroll
-  for (int u = 0; u < D; ++u) issue(0, u);
+  for (int u = 0; u < D; ++u)
+    if (1 + u <= my_k) issue(0, u);
   constexpr int RW = 4;                             // rows in flight per wavefront
 
   for (int b = 0; b * D < my_k; ++b) {
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(kThreads) void lsq_steps_staged_kernel(
         float* Ab = A + (size_t)(s & 1) * bd;
         float* yb = ys + (size_t)(s & 1) * batch;
         land(u, Ab, yb);
-        issue(b + 1, u);
+        if (s + D <= my_k) issue(b + 1, u);         // nothing is requested past the last iteration
         __syncthreads();
         // residuals: RW rows per wavefront at a time, lanes stride over the features
         for (int j0 = wave * RW; j0 < batch; j0 += (kThreads / kWave) * RW) {
