@@ -477,6 +477,10 @@ static hipError_t launch_rows(const GemmArgs& p, int n_groups, hipStream_t s) {
     return launch_one<T, 64, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
   }
   if (wide) return launch_one<T, 128, 128, 2, 2, AKIND, BKIND>(p, n_groups, s);
+  // a narrow layer that would leave compute units idle splits the minibatch rows over two
+  // workgroups instead: the second reader of a weight tile finds it in the L2 of the same XCD
+  if ((long)((p.N + 63) / 64) * n_groups < kComputeUnits)
+    return launch_one<T, 64, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
   return launch_one<T, 128, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
 }
 
