@@ -192,7 +192,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   // 8 XCDs; when the group count is a multiple of 8 all tiles of a group land on one XCD, so the
   // group's activations and weight panel stay in that XCD's L2.
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  const int tiles = tiles_m * tiles_n;
+  const int n_splits = p.k_splits > 1 ? p.k_splits : 1;     // contraction ranges per output tile
+  const int tiles = tiles_m * tiles_n * n_splits;
   int g, tile;
   if ((p.n_groups & 7) == 0) {
     const int slot = blockIdx.x >> 3;
@@ -202,6 +203,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
     g = blockIdx.x / tiles;
     tile = blockIdx.x % tiles;
   }
+  const int ks = tile % n_splits;
+  tile /= n_splits;
   if (p.worker_steps != nullptr && p.step >= p.worker_steps[g]) return;
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
@@ -219,6 +222,17 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
 
   const E* a_src = reinterpret_cast<const E*>(p.a) + (size_t)g * p.a_gs;
   const E* b_src = reinterpret_cast<const E*>(p.b) + (size_t)g * p.b_gs;
+  // this workgroup's contraction range [k_lo, k_lo + Kc): whole tiles per split
+  int Kc = p.Kc;
+  if (n_splits > 1) {
+    const int per = ((p.Kc + BK - 1) / BK + n_splits - 1) / n_splits * BK;
+    const int k_lo = ks * per;
+    Kc = max(0, min(p.Kc - k_lo, per));
+    if (Kc > 0) {                                  // an empty range keeps valid base addresses
+      a_src += (AKIND == OP_CONTIG) ? (size_t)k_lo : (size_t)k_lo * p.lda;
+      b_src += (BKIND == OP_CONTIG) ? (size_t)k_lo : (size_t)k_lo * p.ldb;
+    }
+  }
   const size_t pg = (size_t)g * p.p_gs;
   constexpr bool kIsDw = (AKIND == OP_TRANS && BKIND == OP_TRANS);   // weight-gradient product
   const bool fused = kIsDw && (p.epi == EPI_DW_FUSED);
@@ -261,21 +275,21 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   // prefetch and spends its registers on the streamed weights instead.
   constexpr bool kDeep = !kIsDw;
   constexpr int R = kDeep ? 4 : 1;
-  const int n_k = (p.Kc + BK - 1) / BK;
+  const int n_k = (Kc + BK - 1) / BK;
   uint4 a_r[R][IOA::NPT], b_r[R][IOB::NPT];
   uint32_t a_m[R], b_m[R];                           // validity masks of the register sets
 #pragma unroll
   for (int r = 0; r < R; ++r) { a_m[r] = 0; b_m[r] = 0; }
-  a_m[0] = IOA::fetch(a_r[0], a_src, p.lda, m0, p.M, 0, p.Kc, tid);
-  b_m[0] = IOB::fetch(b_r[0], b_src, p.ldb, n0, p.N, 0, p.Kc, tid);
+  a_m[0] = IOA::fetch(a_r[0], a_src, p.lda, m0, p.M, 0, Kc, tid);
+  b_m[0] = IOB::fetch(b_r[0], b_src, p.ldb, n0, p.N, 0, Kc, tid);
   IOA::stash(a_lds0, a_r[0], a_m[0], tid);
   IOB::stash(b_lds0, b_r[0], b_m[0], tid);
   if constexpr (kDeep) {
 #pragma unroll
     for (int j = 1; j <= R; ++j) {
       if (j < n_k) {
-        a_m[j % R] = IOA::fetch(a_r[j % R], a_src, p.lda, m0, p.M, j * BK, p.Kc, tid);
-        b_m[j % R] = IOB::fetch(b_r[j % R], b_src, p.ldb, n0, p.N, j * BK, p.Kc, tid);
+        a_m[j % R] = IOA::fetch(a_r[j % R], a_src, p.lda, m0, p.M, j * BK, Kc, tid);
+        b_m[j % R] = IOB::fetch(b_r[j % R], b_src, p.ldb, n0, p.N, j * BK, Kc, tid);
       }
     }
   }
@@ -325,8 +339,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
         IOB::stash(b_lds0 + (CUR ^ 1) * B_ELEMS, b_r[SET], b_m[SET], tid);
       }
       if (STEADY || it + 1 + R < n_k) {
-        a_m[SET] = IOA::fetch(a_r[SET], a_src, p.lda, m0, p.M, (it + 1 + R) * BK, p.Kc, tid);
-        b_m[SET] = IOB::fetch(b_r[SET], b_src, p.ldb, n0, p.N, (it + 1 + R) * BK, p.Kc, tid);
+        a_m[SET] = IOA::fetch(a_r[SET], a_src, p.lda, m0, p.M, (it + 1 + R) * BK, Kc, tid);
+        b_m[SET] = IOB::fetch(b_r[SET], b_src, p.ldb, n0, p.N, (it + 1 + R) * BK, Kc, tid);
       }
       __syncthreads();
     };
@@ -349,8 +363,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
     for (int it = 0; it < n_k; ++it) {         // single LDS stage, next tile prefetched in registers
       const bool more = it + 1 < n_k;
       if (more) {
-        a_m[0] = IOA::fetch(a_r[0], a_src, p.lda, m0, p.M, (it + 1) * BK, p.Kc, tid);
-        b_m[0] = IOB::fetch(b_r[0], b_src, p.ldb, n0, p.N, (it + 1) * BK, p.Kc, tid);
+        a_m[0] = IOA::fetch(a_r[0], a_src, p.lda, m0, p.M, (it + 1) * BK, Kc, tid);
+        b_m[0] = IOB::fetch(b_r[0], b_src, p.ldb, n0, p.N, (it + 1) * BK, Kc, tid);
       }
       compute(0);
       if (more) {
@@ -413,7 +427,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
     for (int j = 0; j < TN; ++j) {
       const int n = n0 + (wn * TN + j) * 32 + lr32;
       const bool n_ok = n < p.out_cols;
-      const float bn = (bias != nullptr) ? bias[n_ok ? n : 0] : 0.0f;
+      // partial sums of a split contraction carry no bias: the loss head adds it once
+      const float bn = (bias != nullptr && n_splits == 1) ? bias[n_ok ? n : 0] : 0.0f;
       // all loads of the tile first (they may not be reordered across the stores below)
       float h[16];
       if (p.epi == EPI_DX) {
@@ -433,7 +448,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
         if (p.epi == EPI_FWD_HIDDEN) {
           reinterpret_cast<E*>(p.out)[o] = to_elem<T>(act_fwd(c + bn, p.act));
         } else if (p.epi == EPI_FWD_LOGITS) {
-          reinterpret_cast<float*>(p.out)[o] = c + bn;
+          reinterpret_cast<float*>(p.out)[(size_t)ks * p.split_stride + o] = c + bn;
         } else {  // EPI_DX
           reinterpret_cast<E*>(p.out)[o] = to_elem<T>(c * act_bwd_from_h(h[v], p.act));
         }
@@ -457,7 +472,8 @@ static hipError_t launch_one(GemmArgs p, int n_groups, hipStream_t s) {
     configured = true;
   }
   p.n_groups = n_groups;
-  const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  if (p.k_splits > 1 && p.epi != EPI_FWD_LOGITS) return hipErrorInvalidValue;
+  const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN) * (p.k_splits > 1 ? p.k_splits : 1);
   hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles * n_groups)), dim3(kThreads), kLds, s, p);
   return hipGetLastError();
 }
@@ -482,6 +498,32 @@ static hipError_t launch_rows(const GemmArgs& p, int n_groups, hipStream_t s) {
   if ((long)((p.N + 63) / 64) * n_groups < kComputeUnits)
     return launch_one<T, 64, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
   return launch_one<T, 128, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
+}
+
+// Output tiles of the batch-row launch launch_rows() would make for p.
+static long rows_launch_tiles(const GemmArgs& p, int n_groups) {
+  int bm, bn;
+  if (p.M <= 32) { bm = 32; bn = 128; }
+  else {
+    const bool wide = (long)((p.N + 127) / 128) * n_groups * ((p.M + 127) / 128) >= kComputeUnits;
+    const bool narrow = (long)((p.N + 63) / 64) * n_groups < kComputeUnits;
+    bm = (p.M <= 64 || (!wide && narrow)) ? 64 : 128;
+    bn = wide ? 128 : 64;
+  }
+  return (long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn) * n_groups;
+}
+
+// A logits product that leaves most compute units idle (few classes) cuts its contraction into
+// 2 or 4 ranges of whole tiles, every range non-empty and at least two tiles long.
+int gemm_logit_splits(const GemmArgs& p, int n_groups, bool bf16) {
+  const int bk = bf16 ? TBF16::BK : TF32::BK;
+  const int n_k = (p.Kc + bk - 1) / bk;
+  const long wgs = rows_launch_tiles(p, n_groups);
+  for (int s = kMaxLogitSplits; s >= 2; s >>= 1) {
+    const int per = (n_k + s - 1) / s;
+    if (wgs * s <= kComputeUnits && per >= 2 && (long)per * (s - 1) < n_k) return s;
+  }
+  return 1;
 }
 
 hipError_t launch_gemm_fwd(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s) {

@@ -67,7 +67,8 @@ __global__ __launch_bounds__(kThreads) void sample_indices_kernel(int32_t* __res
 //   row_loss[b] = -log softmax(z_b)[c_b],   delta = (softmax(z) - onehot(c)) / B
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
-    const float* __restrict__ logits, const int32_t* __restrict__ yb, void* __restrict__ delta,
+    const float* __restrict__ logits, int n_parts, long part_stride, const float* __restrict__ bias,
+    long bias_gs, const int32_t* __restrict__ yb, void* __restrict__ delta,
     float* __restrict__ row_loss, int batch, int n_classes, int ldc,
     const int* __restrict__ worker_steps, int step) {
   const int g = blockIdx.y;
@@ -77,24 +78,69 @@ __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
   if (b >= batch) return;
   const float inv_b = 1.0f / (float)batch;
   const size_t r = (size_t)g * batch + b;
-  const float* z = logits + r * ldc;
+  // logit of class c: the product's output, or (split contraction) the bias plus the partial
+  // sums in split order
+  const float* bias_g = bias != nullptr ? bias + (size_t)g * bias_gs : nullptr;
+  auto logit = [&](int c) {
+    float z = bias_g != nullptr ? bias_g[c] : 0.0f;
+    for (int s = 0; s < n_parts; ++s) z += logits[(size_t)s * part_stride + r * ldc + c];
+    return z;
+  };
+  const int label = yb[r];
+  constexpr int ZR = 16;                             // classes per lane held in registers
+  if (n_classes <= ZR * kWave) {
+    float z[ZR];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < ZR; ++q) {
+      const int c = lane + kWave * q;
+      z[q] = (kWave * q < n_classes && c < n_classes) ? logit(c) : -INFINITY;
+      mx = fmaxf(mx, z[q]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float zl = 0.0f, se = 0.0f;                      // the label's logit lives in one lane
+#pragma unroll
+    for (int q = 0; q < ZR; ++q) {
+      const int c = lane + kWave * q;
+      if (c == label && c < n_classes) zl = z[q];
+      z[q] = (kWave * q < n_classes && c < n_classes) ? expf(z[q] - mx) : 0.0f;
+      se += z[q];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      se += __shfl_xor(se, o);
+      zl += __shfl_xor(zl, o);
+    }
+#pragma unroll
+    for (int q = 0; q < ZR; ++q) {
+      const int c = lane + kWave * q;
+      if (kWave * q < ldc && c < ldc) {
+        const float d = c < n_classes ? (z[q] / se - (c == label ? 1.0f : 0.0f)) * inv_b : 0.0f;
+        if (BF16) reinterpret_cast<uint16_t*>(delta)[r * ldc + c] = f32_to_bf16_rne(d);
+        else reinterpret_cast<float*>(delta)[r * ldc + c] = d;
+      }
+    }
+    // an out-of-range label selects nothing (zl stays 0)
+    if (lane == 0) row_loss[r] = (mx + logf(se)) - zl;
+    return;
+  }
   float mx = -INFINITY;
-  for (int c = lane; c < n_classes; c += kWave) mx = fmaxf(mx, z[c]);
+  for (int c = lane; c < n_classes; c += kWave) mx = fmaxf(mx, logit(c));
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
   float se = 0.0f;
-  for (int c = lane; c < n_classes; c += kWave) se += expf(z[c] - mx);
+  for (int c = lane; c < n_classes; c += kWave) se += expf(logit(c) - mx);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
-  const int label = yb[r];
   for (int c = lane; c < ldc; c += kWave) {
     float d = 0.0f;
-    if (c < n_classes) d = (expf(z[c] - mx) / se - (c == label ? 1.0f : 0.0f)) * inv_b;
+    if (c < n_classes) d = (expf(logit(c) - mx) / se - (c == label ? 1.0f : 0.0f)) * inv_b;
     if (BF16) reinterpret_cast<uint16_t*>(delta)[r * ldc + c] = f32_to_bf16_rne(d);
     else reinterpret_cast<float*>(delta)[r * ldc + c] = d;
   }
   // an out-of-range label must not index outside the row
-  const float z_label = (label >= 0 && label < n_classes) ? z[label] : 0.0f;
+  const float z_label = (label >= 0 && label < n_classes) ? logit(label) : 0.0f;
   if (lane == 0) row_loss[r] = (mx + logf(se)) - z_label;
 }
 
@@ -133,16 +179,17 @@ hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long r
   return hipGetLastError();
 }
 
-hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* row_loss,
+hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_stride, const float* bias,
+                               long bias_gs, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
                                const int* worker_steps, int step, hipStream_t s) {
   dim3 grid((batch + kThreads / kWave - 1) / (kThreads / kWave), n_workers);
   if (bf16)
-    hipLaunchKernelGGL(softmax_xent_kernel<true>, grid, dim3(kThreads), 0, s, logits, yb, delta,
-                       row_loss, batch, n_classes, ldc, worker_steps, step);
+    hipLaunchKernelGGL(softmax_xent_kernel<true>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
+                       bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step);
   else
-    hipLaunchKernelGGL(softmax_xent_kernel<false>, grid, dim3(kThreads), 0, s, logits, yb, delta,
-                       row_loss, batch, n_classes, ldc, worker_steps, step);
+    hipLaunchKernelGGL(softmax_xent_kernel<false>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
+                       bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step);
   return hipGetLastError();
 }
 

@@ -122,7 +122,7 @@ void build_carve(const prsgd_config* c_in, const Layout& lo, Carve* cv) {
       cv->delta[l] = take(n * b * lo.ld[l] * es);
     }
     cv->delta[L] = take(n * b * lo.ld[L] * es);
-    cv->logits = take(n * b * lo.ld[L] * 4);
+    cv->logits = take((size_t)kMaxLogitSplits * n * b * lo.ld[L] * 4);   // room for split partial sums
     if (bf16) {
       cv->shadow = take(n * (size_t)lo.m_pad * 2);
       cv->mean_shadow = take((size_t)lo.m_pad * 2);
@@ -294,6 +294,8 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
   base.bias_gs = ctx->src_stride();
 
   // forward
+  int logit_parts = 1;
+  const long logit_part_stride = (long)N * B * lo.ld[L];
   for (int l = 1; l <= L; ++l) {
     GemmArgs p = base;
     p.a = act_in(l - 1); p.a_gs = (long)B * lo.ld[l - 1]; p.lda = lo.ld[l - 1];
@@ -304,12 +306,18 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
     p.b_off = lo.b_off[l - 1];
     p.out_gs = (long)B * lo.ld[l]; p.ldo = lo.ld[l]; p.out_cols = lo.ld[l];
     if (l < L) { p.epi = EPI_FWD_HIDDEN; p.out = ctx->at<void>(cv.h[l]); }
-    else { p.epi = EPI_FWD_LOGITS; p.out = ctx->at<void>(cv.logits); }
+    else {
+      p.epi = EPI_FWD_LOGITS; p.out = ctx->at<void>(cv.logits);
+      logit_parts = gemm_logit_splits(p, N, bf16);
+      p.k_splits = logit_parts; p.split_stride = logit_part_stride;
+    }
     LAUNCH(ctx, KK_FWD, launch_gemm_fwd(p, N, bf16, s));
   }
 
   LAUNCH(ctx, KK_LOSS,
-         launch_softmax_xent(ctx->at<float>(cv.logits), ctx->at<int32_t>(cv.yb),
+         launch_softmax_xent(ctx->at<float>(cv.logits), logit_parts, logit_part_stride,
+                             logit_parts > 1 ? ctx->src() + lo.b_off[L - 1] : nullptr, ctx->src_stride(),
+                             ctx->at<int32_t>(cv.yb),
                              ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.row_loss), N, B, lo.d[L],
                              lo.ld[L], bf16, worker_steps, step, s));
 

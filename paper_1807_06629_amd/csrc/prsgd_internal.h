@@ -59,7 +59,13 @@ struct GemmArgs {
   const void* aux; long aux_gs; int ldaux;
   // Algorithm 3: group g is skipped once step >= worker_steps[g] (nullptr = all active)
   const int* worker_steps; int step;
+  // logits product of a narrow last layer: the contraction is cut into k_splits ranges, split s
+  // writes its partial sums (no bias) at out + s * split_stride; the loss head adds them up
+  int k_splits; long split_stride;
 };
+// contraction splits the forward launcher wants for the logits product described by p
+int gemm_logit_splits(const GemmArgs& p, int n_groups, bool bf16);
+constexpr int kMaxLogitSplits = 4;
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
@@ -122,7 +128,8 @@ hipError_t launch_gather(const float* features, const int32_t* labels, void* xb,
                          hipStream_t s);
 hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long rows, int64_t t_first,
                                  int n_steps, int32_t* out, hipStream_t s);
-hipError_t launch_softmax_xent(const float* logits, const int32_t* yb, void* delta, float* row_loss,
+hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_stride, const float* bias,
+                               long bias_gs, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
                                const int* worker_steps, int step, hipStream_t s);
 hipError_t launch_loss_mean(const float* row_loss, float* losses, int n_workers, int batch,
