@@ -136,20 +136,20 @@ def cpu_baseline(w, inp, budget_s=20.0):
 
 def restart_average_at_hbm_scale(prsgd, drivers, get_workload, make_inputs, reps=20):
     """The restart kernels (eq. 2) timed on a replica set far larger than the caches: the
-    largest workload's replicas ([8][54.4M] fp32 + bf16 shadow) with a token data shard.
-    `average` = read every replica, overwrite every replica (4.36 GB per pass); `restart_mean` =
-    the deferred-broadcast form, every replica read, the average written once (2.07 GB).  HIP
-    events on the library's stream, through the library's own profiling."""
+    largest workload's replicas ([8][54.4M] fp32 + bf16 shadow) with a token data shard, in the
+    alternation they run in (one local iteration, then the restart).  `average` = read every
+    replica, overwrite every replica (4.36 GB per pass); `restart_mean` = the deferred-broadcast
+    form, every replica read, the average written once (2.07 GB).  HIP events on the library's
+    stream, through the library's own profiling."""
     w = get_workload("c5").scaled(rows_per_worker=64, batch=8)
     h = drivers.open_workload(w, make_inputs(w), device="cuda:0")
-    out = {"workload": "replica set of c5: N=8, m=54440936, fp32 master + bf16 shadow"}
+    out = {"workload": "replica set of c5: N=8, m=54440936, fp32 master + bf16 shadow; "
+                       "one local iteration (B=8) between restarts"}
     for lazy, label in ((False, "average"), (True, "restart_mean")):
         prsgd.prsgd_set_lazy_restart(h, lazy)
         def once():
+            prsgd.prsgd_local_steps(h, 1)
             prsgd.prsgd_average(h)
-            if lazy:
-                prsgd.prsgd_set_lazy_restart(h, False)   # broadcast (not timed under this label)
-                prsgd.prsgd_set_lazy_restart(h, True)
         for _ in range(3):
             once()
         prsgd.prsgd_profile_enable(h, True)
