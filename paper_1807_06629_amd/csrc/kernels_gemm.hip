@@ -521,7 +521,7 @@ int gemm_logit_splits(const GemmArgs& p, int n_groups, bool bf16) {
   const long wgs = rows_launch_tiles(p, n_groups);
   for (int s = kMaxLogitSplits; s >= 2; s >>= 1) {
     const int per = (n_k + s - 1) / s;
-    if (wgs * s <= kComputeUnits && per >= 2 && (long)per * (s - 1) < n_k) return s;
+    if (wgs * s <= 2 * kComputeUnits && per >= 2 && (long)per * (s - 1) < n_k) return s;
   }
   return 1;
 }
