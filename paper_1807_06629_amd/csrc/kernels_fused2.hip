@@ -118,50 +118,12 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   const float* feat = p.features + (size_t)i * p.rows * d0;
   const int32_t* lab = p.labels + (size_t)i * p.rows;
 
-  // ---- load the slice: W_1 to registers, W_2 / b_1 / b_2 to LDS -------------------------------
-  float w1[KBI][NT][4];
-#pragma unroll
-  for (int kbi = 0; kbi < KBI; ++kbi) {
-    const int kb = wave + kTW * kbi;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const int k = 16 * kb + 4 * q4 + s;
-        const bool ok = kb < KB && k < d0;
-        const float v = prm0[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
-        w1[kbi][nt][s] = ok ? v : 0.0f;
-      }
-  }
-  for (int e = tid; e < W * D2P; e += kTT) {
-    const int n = e / D2P, c = e % D2P;
-    w2[e] = c < d2 ? prm0[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
-  }
-  if (tid < W) b1[tid] = prm0[p.b1_off + j * W + tid];
-  if (tid < D2P) b2[tid] = tid < d2 ? prm0[p.b2_off + tid] : 0.0f;
-  // velocity of the slice, same places
-  float* vel = MOM ? p.vel + (size_t)i * p.m_pad : nullptr;
-  float vw1[MOM ? KBI : 1][NT][4];
-  if constexpr (MOM) {
-#pragma unroll
-    for (int kbi = 0; kbi < KBI; ++kbi) {
-      const int kb = wave + kTW * kbi;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int k = 16 * kb + 4 * q4 + q;
-          const bool ok = kb < KB && k < d0;
-          const float v = vel[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
-          vw1[kbi][nt][q] = ok ? v : 0.0f;
-        }
-    }
-    for (int e = tid; e < W * D2P; e += kTT) {
-      const int n = e / D2P, c = e % D2P;
-      vw2[e] = c < d2 ? vel[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
-    }
-    if (tid < W) vb1[tid] = vel[p.b1_off + j * W + tid];
-    if (tid < D2P) vb2[tid] = tid < d2 ? vel[p.b2_off + tid] : 0.0f;
+  // Rows of the first iteration first: their features, their labels and the parameter slice are
+  // then requested together, so that the launch pays one memory latency instead of three.
+  int row_first = 0;
+  if (tid < B) {
+    row_first = sample_row(p.seed, (uint32_t)i, p.t0 + 1, (uint32_t)tid, p.log2n);
+    rows[tid] = row_first;
   }
   for (int e = tid; e < MR * ldx; e += kTT) X[e] = 0.0f;     // pad rows / columns stay zero
   if (tid == 0) flag[0] = 0;
@@ -240,17 +202,62 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
         __builtin_amdgcn_global_load_lds((gptr_t)(feat + (size_t)rows[r] * d0 + 4 * c), (lptr_t)(X + lds_off),
                                          16, 0, 0);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the data is in LDS before the next barrier
+  };
+  auto gather_direct_wait = [&]() {                        // the data is in LDS before the next barrier
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
-  // rows, labels and features of the first iteration
-  if (tid < B) {
-    const int r = sample_row(p.seed, (uint32_t)i, p.t0 + 1, (uint32_t)tid, p.log2n);
-    rows[tid] = r;
-    ylab[tid] = lab[r];
+  // labels and features of the first iteration, requested before the parameter slice
+  int lab_first = 0;
+  if (tid < B) lab_first = lab[row_first];
+  if constexpr (PF > 0) gather_issue(rows, 0); else gather_direct();
+  // ---- load the slice: W_1 to registers, W_2 / b_1 / b_2 to LDS -------------------------------
+  float w1[KBI][NT][4];
+#pragma unroll
+  for (int kbi = 0; kbi < KBI; ++kbi) {
+    const int kb = wave + kTW * kbi;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int k = 16 * kb + 4 * q4 + s;
+        const bool ok = kb < KB && k < d0;
+        const float v = prm0[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
+        w1[kbi][nt][s] = ok ? v : 0.0f;
+      }
   }
-  __syncthreads();
-  if constexpr (PF > 0) { gather_issue(rows, 0); gather_store(0); gather_rest(rows); } else { gather_direct(); }
+  for (int e = tid; e < W * D2P; e += kTT) {
+    const int n = e / D2P, c = e % D2P;
+    w2[e] = c < d2 ? prm0[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
+  }
+  if (tid < W) b1[tid] = prm0[p.b1_off + j * W + tid];
+  if (tid < D2P) b2[tid] = tid < d2 ? prm0[p.b2_off + tid] : 0.0f;
+  // velocity of the slice, same places
+  float* vel = MOM ? p.vel + (size_t)i * p.m_pad : nullptr;
+  float vw1[MOM ? KBI : 1][NT][4];
+  if constexpr (MOM) {
+#pragma unroll
+    for (int kbi = 0; kbi < KBI; ++kbi) {
+      const int kb = wave + kTW * kbi;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int k = 16 * kb + 4 * q4 + q;
+          const bool ok = kb < KB && k < d0;
+          const float v = vel[p.w1_off + (ok ? (size_t)k * p.ld1 + j * W + nt * 16 + n16 : (size_t)0)];
+          vw1[kbi][nt][q] = ok ? v : 0.0f;
+        }
+    }
+    for (int e = tid; e < W * D2P; e += kTT) {
+      const int n = e / D2P, c = e % D2P;
+      vw2[e] = c < d2 ? vel[p.w2_off + (size_t)(j * W + n) * p.ld2 + c] : 0.0f;
+    }
+    if (tid < W) vb1[tid] = vel[p.b1_off + j * W + tid];
+    if (tid < D2P) vb2[tid] = tid < d2 ? vel[p.b2_off + tid] : 0.0f;
+  }
+  if (tid < B) ylab[tid] = lab_first;
+  if constexpr (PF > 0) { gather_store(0); gather_rest(rows); } else { gather_direct_wait(); }
   // rows and labels of the second iteration (the pipeline runs one iteration ahead)
   int lab_next = 0;
   if (PF > 0 && my_k > 1 && tid < B) {
@@ -566,6 +573,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
         }
         __syncthreads();
         gather_direct();
+        gather_direct_wait();
       }
       __syncthreads();
     }
