@@ -10,8 +10,9 @@
 //     registers of the weight-gradient product: eq. (3) for W_1 is a register-to-register fma;
 //   - its slices of b_1 and W_2 (and a private copy of b_2) live in LDS;
 //   - per iteration it computes its slice of the hidden layer on the minibatch held in LDS and
-//     contributes a partial logit block; the next iteration's rows are drawn and gathered
-//     (HBM -> registers) meanwhile.  One team-wide barrier per iteration
+//     contributes a partial logit block; the next iteration's rows are drawn meanwhile and, for
+//     shapes with registers to spare, gathered (HBM -> registers) meanwhile as well -- otherwise
+//     at the end of the iteration, with loads that write LDS directly.  One team-wide barrier per iteration
 //     (a counter in HBM, bounded spin) lets every member sum the P partials in fixed order;
 //     everything after that (softmax, both delta blocks, dW_2, db, dW_1) is local to the slice.
 // Teams of different workers never synchronise.  Summation orders are fixed, so a run is
@@ -25,15 +26,6 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr unsigned kSpinLimit = 1u << 22;     // bounded wait: a lost team member aborts the launch
 constexpr int kTT = 512;                      // threads per team member: two wavefronts per SIMD, so
-#ifndef PRSGD_F2_PF_WIDE
-#define PRSGD_F2_PF_WIDE 0         // prefetched vectors per thread and batch tile, shapes with many row blocks
-#endif
-#ifndef PRSGD_F2_DIRECT_G
-#define PRSGD_F2_DIRECT_G 8
-#endif
-#ifndef PRSGD_F2_PF_MOM
-#define PRSGD_F2_PF_MOM 0          // the same with momentum (velocity registers on top)
-#endif
 constexpr int kTW = kTT / kWave;              // that the latency-bound phases of one overlap the other's
 constexpr int kAgentScope = 16;               // buffer-load cache policy: the sc1 bit (agent scope)
 
@@ -140,11 +132,10 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   // 16-byte column pc of rows rg, rg + ng, rg + 2 ng, ... (a row is at most 256 vectors wide).
   // Rows B .. MR-1 of X receive a copy of the first drawn row: finite values that only ever meet
   // zero deltas.
-  // TV vectors per thread make up a minibatch; PF of them are requested an iteration early (0 = no
-  // prefetch): all of them where registers allow, otherwise half, and the rest at the end of the
-  // iteration through the same registers
-  constexpr int TV = 8 * MT;
-  constexpr int PF = MT > 2 ? 0 : (KBI * NT > 4) ? (MOM ? PRSGD_F2_PF_MOM : PRSGD_F2_PF_WIDE) * MT : TV;
+  // PF vectors per thread make up a minibatch and are requested an iteration early; 0 = no
+  // prefetch, for the shapes whose W_1 slice leaves no registers for it (measured on 784-256-10,
+  // seven row blocks per wavefront: 200 us per 16-iteration launch without, 219 us with)
+  constexpr int PF = (MT > 2 || KBI * NT > 4) ? 0 : 8 * MT;
   const int v4 = d0 >> 2, total4 = B * v4;
   int cw_log = 5;                                          // ng <= 16 divides MR
   while ((1 << cw_log) < v4) ++cw_log;
@@ -152,37 +143,28 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   const bool pc_ok = pc < v4;
   int rg = tid >> cw_log;
   f32x4_t pre[PF > 0 ? PF : 1];
-  auto gather_issue = [&](const int* rws, int ub) {         // vectors ub .. ub + PF - 1
+  auto gather_issue = [&](const int* rws) {
     // opaque copy: keeps the per-vector addresses and predicates from being hoisted out of the
     // iteration loop into (spilled) registers
     asm volatile("" : "+v"(rg));
     const float* src = feat + (pc_ok ? 4 * pc : 0);
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
-      if (ng * (ub + u) < B) {                             // uniform over the workgroup
-        const int r = rg + ng * (ub + u);
+      if (ng * u < B) {                                    // uniform over the workgroup
+        const int r = rg + ng * u;
         pre[u] = *reinterpret_cast<const f32x4_t*>(src + (size_t)rws[r < B ? r : 0] * d0);
       }
     }
   };
-  auto gather_store = [&](int ub) {
+  auto gather_store = [&]() {
     asm volatile("" : "+v"(rg));
     if (pc_ok) {
-      float* dst = X + (size_t)(rg + ng * ub) * ldx + 4 * pc;
+      float* dst = X + (size_t)rg * ldx + 4 * pc;
       const int step = ng * ldx;
 #pragma unroll
       for (int u = 0; u < PF; ++u) {
-        if (ng * (ub + u) < B) *reinterpret_cast<f32x4_t*>(dst) = pre[u];
+        if (ng * u < B) *reinterpret_cast<f32x4_t*>(dst) = pre[u];
         dst += step;
-      }
-    }
-  };
-  // the part of a minibatch that was not requested early
-  auto gather_rest = [&](const int* rws) {
-    if constexpr (PF > 0) {
-      for (int ub = PF; ub < TV; ub += PF) {
-        gather_issue(rws, ub);
-        gather_store(ub);
       }
     }
   };
@@ -210,7 +192,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
   // labels and features of the first iteration, requested before the parameter slice
   int lab_first = 0;
   if (tid < B) lab_first = lab[row_first];
-  if constexpr (PF > 0) gather_issue(rows, 0); else gather_direct();
+  if constexpr (PF > 0) gather_issue(rows); else gather_direct();
   // ---- load the slice: W_1 to registers, W_2 / b_1 / b_2 to LDS -------------------------------
   float w1[KBI][NT][4];
 #pragma unroll
@@ -257,7 +239,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     if (tid < D2P) vb2[tid] = tid < d2 ? vel[p.b2_off + tid] : 0.0f;
   }
   if (tid < B) ylab[tid] = lab_first;
-  if constexpr (PF > 0) { gather_store(0); gather_rest(rows); } else { gather_direct_wait(); }
+  if constexpr (PF > 0) gather_store(); else gather_direct_wait();
   // rows and labels of the second iteration (the pipeline runs one iteration ahead)
   int lab_next = 0;
   if (PF > 0 && my_k > 1 && tid < B) {
@@ -283,7 +265,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     // registers: their issue stalls once the memory pipeline is full, and the matrix products
     // of the forward slice below do not need that pipeline
     if constexpr (PF > 0) {
-      if (s < my_k) gather_issue(rows_ahead + ((s + 1) & 1) * MR, 0);
+      if (s < my_k) gather_issue(rows_ahead + ((s + 1) & 1) * MR);
     }
     // (c) forward slice: contraction index of MFMA step q is k = 16 kb + 4 q4 + q.  Row blocks
     // past the last one hold zero weights and re-read the last block, so the loop is branch-free.
@@ -554,8 +536,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
     if (s < my_k) {
       if constexpr (PF > 0) {
         const int* rows_next = rows_ahead + ((s + 1) & 1) * MR;
-        gather_store(0);
-        gather_rest(rows_next);
+        gather_store();
         if (tid < B) {
           rows[tid] = rows_next[tid];
           ylab[tid] = lab_next;
