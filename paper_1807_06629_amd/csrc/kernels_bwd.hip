@@ -15,6 +15,8 @@
 // products on the matrix cores (v_mfma_f32_32x32x16_bf16), passes the dW tile through LDS into the
 // row-major layout of the 16-byte weight loads, and writes master and shadow back.  Weight tiles
 // are fetched two tiles ahead, D_l tiles (L2-resident: B x d_l bf16) one tile ahead.
+#include <atomic>
+
 #include "prsgd_internal.h"
 
 namespace prsgd {
@@ -327,12 +329,12 @@ hipError_t launch_bwd_one(const BwdArgs& p, hipStream_t s) {
   constexpr size_t kLds =
       sizeof(uint16_t) * (BR * SH + BR * SD + BMK * SW) + sizeof(float) * (BMK * SG + 4 * BN);
   auto kernel = grouped_bwd_kernel<MB, DX, S, MOM>;
-  static bool configured = false;
-  if (!configured) {
+  static std::atomic<bool> configured{false};   // per kernel instance; setting it twice is harmless
+  if (!configured.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e != hipSuccess) return e;
-    configured = true;
+    configured.store(true, std::memory_order_release);
   }
   const int tiles = (p.K + BMK - 1) / BMK;
   hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles * p.n_groups)), dim3(kThreads), kLds, s, p);

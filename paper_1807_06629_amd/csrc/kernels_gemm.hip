@@ -12,6 +12,7 @@
 // (v_mfma_f32_32x32x16_bf16 or v_mfma_f32_32x32x2_f32).  Operand tiles are staged through LDS in
 // their natural memory orientation with 16-byte global loads; an operand whose contraction
 // index is the strided one is transposed while its MFMA fragments are read out of LDS.
+#include <atomic>
 #include <type_traits>
 
 #include "prsgd_internal.h"
@@ -464,12 +465,13 @@ static hipError_t launch_one(GemmArgs p, int n_groups, hipStream_t s) {
   constexpr size_t kLds =
       kStages * sizeof(E) * (TileShape<T, BM, AKIND>::kElems + TileShape<T, BN, BKIND>::kElems);
   auto kernel = grouped_gemm_kernel<T, BM, BN, WM, WN, AKIND, BKIND>;
-  static bool configured = false;              // double-buffered tiles can exceed the 64 KB default
-  if (!configured) {
+  // double-buffered tiles can exceed the 64 KB default; setting the limit twice is harmless
+  static std::atomic<bool> configured{false};
+  if (!configured.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e != hipSuccess) return e;
-    configured = true;
+    configured.store(true, std::memory_order_release);
   }
   p.n_groups = n_groups;
   if (p.k_splits > 1 && p.epi != EPI_FWD_LOGITS) return hipErrorInvalidValue;
