@@ -12,11 +12,17 @@ Pins (tests/test_oracle_*.py, all run without a GPU):
   Algorithm 1       I=1 == mini-batch SGD with the averaged gradient; N=1 == SGD;
                     eq. (5) mean recursion; eq. (6) restart identity; replicas
                     equal after every restart
-  Algorithms 2, 3   reduce to Algorithm 1 for constant (gamma, K) / equal I_i
+  Algorithms 2, 3   reduce to Algorithm 1 for constant (gamma, K) / equal I_i; Algorithm 2 with
+                    epochs of different lengths and rates against a loop written out in the
+                    test and against the closed form of a one-row least-squares problem;
+                    Theorem 2's K^s against its exact integer definition
   momentum          mu = 0 is Algorithm 1; geometric closed form under a constant gradient;
                     N = 1 against an independently written heavy-ball loop; I = 1 with
                     averaged buffers == momentum SGD on the averaged gradient; mean recursion
-  bf16 rounding     torch's float32 -> bfloat16 conversion
+  bf16 rounding     torch's float32 -> bfloat16 conversion (NaN and infinity included)
+  bf16 operand mode nets with hidden layers against an emulation built from torch.bfloat16 casts;
+                    a hand-sized net whose expected values are exact binary fractions and which
+                    fails when any single rounding point is left out
 
 Parity unpinned: the long-horizon (thousands of non-convex steps) trajectory has
 no reference other than this oracle itself.

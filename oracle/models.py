@@ -30,13 +30,16 @@ import numpy as np
 
 
 def round_bf16(a: np.ndarray) -> np.ndarray:
-    """Round float values to the nearest bfloat16 (ties to even); returns float64."""
-    f = np.asarray(a, dtype=np.float64).astype(np.float32)
+    """Round float values to the nearest bfloat16 (ties to even); returns float64.
+    A NaN stays a NaN (the rounding bias must not carry its payload into the exponent)."""
+    with np.errstate(invalid="ignore"):                       # signalling NaNs in the cast
+        f = np.asarray(a, dtype=np.float64).astype(np.float32)
     bits = f.view(np.uint32).astype(np.uint64)
     lsb = (bits >> np.uint64(16)) & np.uint64(1)
     rounded = (bits + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
-    out = rounded.astype(np.uint32).view(np.float32)
-    return out.astype(np.float64).reshape(np.shape(a))
+    out = rounded.astype(np.uint32).view(np.float32).astype(np.float64)
+    out = np.where(np.isnan(f), np.nan, out)
+    return out.reshape(np.shape(a))
 
 
 def lsq_loss_grad(x: np.ndarray, a_b: np.ndarray, y_b: np.ndarray) -> Tuple[float, np.ndarray]:

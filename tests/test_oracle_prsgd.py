@@ -161,6 +161,51 @@ def test_time_varying_with_constant_schedule_is_algorithm1():
     assert b["t"] == 20
 
 
+def test_time_varying_rates_against_an_independent_loop():
+    # Algorithm 2 with epochs of different lengths AND different rates, written out here with
+    # nothing but the gradient and the row sampler: epoch s starts every worker from the mean of
+    # the previous epoch's final points, then takes K^s steps at rate gamma^s; iterations are
+    # numbered through.  A loop that kept gamma^1, or K^1, for every epoch fails.
+    w, inp = _small("c2", **MLP)
+    lengths, rates = [3, 1, 4, 2], [0.08, 0.02, 0.05, 0.11]
+    out = run_time_varying(**_args(w, inp), epoch_lengths=lengths, epoch_rates=rates)
+    xs = [inp["x0"].astype(np.float64).copy() for _ in range(w.n_workers)]
+    t0 = 0
+    for k_s, gamma_s in zip(lengths, rates):
+        start = sum(xs) / w.n_workers
+        for i in range(w.n_workers):
+            x = start.copy()
+            for t in range(t0 + 1, t0 + k_s + 1):
+                rows = sample_rows(w.index_seed, i, t, w.batch, w.rows_per_worker)
+                x = x - gamma_s * loss_grad(w.model, x, w.dims, w.activation,
+                                            inp["features"][i][rows], inp["targets"][i][rows])[1]
+            xs[i] = x
+        t0 += k_s
+    assert out["t"] == sum(lengths)
+    assert np.allclose(out["x"], np.stack(xs), rtol=1e-12, atol=1e-14)
+    # and the wrong loops really differ
+    flat = run_time_varying(**_args(w, inp), epoch_lengths=lengths, epoch_rates=[rates[0]] * 4)
+    assert np.abs(flat["x"] - out["x"]).max() > 1e-4
+
+
+def test_time_varying_rates_closed_form_on_a_one_row_least_squares_problem():
+    # one worker whose shard has a single row a, target y: every minibatch is that row, the
+    # residual r = a.x - y obeys r <- r (1 - gamma |a|^2), so after the epochs
+    #   r_T = r_0 * prod_s (1 - gamma^s |a|^2)^(K^s)
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((1, 1, 5)).astype(np.float32)
+    y = rng.standard_normal((1, 1)).astype(np.float32)
+    lengths, rates = [2, 5, 1, 3], [0.30, 0.05, 0.21, 0.11]
+    out = run_time_varying("lsq", (5,), "none", a, y, np.zeros(5, np.float32), 1, 3,
+                           epoch_lengths=lengths, epoch_rates=rates, seed=4)
+    a64, y64 = a[0, 0].astype(np.float64), float(y[0, 0])
+    want = -y64
+    for k_s, g_s in zip(lengths, rates):
+        want *= (1.0 - g_s * (a64 @ a64)) ** k_s
+    assert a64 @ out["x"][0] - y64 == pytest.approx(want, rel=1e-11)
+    assert out["t"] == 11
+
+
 def test_time_varying_schedule_theorem2():
     ks, gs = time_varying_schedule(30, 2)
     assert ks[0] == 1 and gs[0] == 2.0                      # s=1: ceil(1/2)=1, N/1
