@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Throughput benchmark of the PR-SGD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--interval I]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5] [--interval I]
 
 A step is one iteration of Algorithm 1 over all N workers: seeded minibatch draw, forward,
 backward, local update (eq. 3), plus the restart average (eq. 2) after every I-th
-iteration.  Inputs are synthetic and resident in HBM before the timed region.  Prints ONE JSON
-line: samples/s over the N replicas, a roofline record for the kernel that dominates the
-step, the restart-average bandwidth, and the CPU oracle timed on a bounded sample of the same
-workload as a reported baseline.
+iteration.  The default workload is the largest configuration (c5: N = 8 replicas of a
+4096-4096-4096-4096-1000 ReLU MLP, bf16 matrix operands, B = 128, I = 16), the one whose replica
+set is far larger than the caches.  Inputs are synthetic and resident in HBM before the timed
+region.  Prints ONE JSON line: samples/s over the N replicas, a roofline record for the kernel
+that dominates the step, the restart-average and stand-alone update bandwidths at HBM scale, and
+the CPU oracle timed on a bounded sample of the same workload as a reported baseline.
 """
 from __future__ import annotations
 
@@ -31,7 +33,11 @@ KERNEL_SYMBOL = {
     "gemm_dx": "grouped_gemm_kernel<.., OP_CONTIG, OP_CONTIG>",
     "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>", "gemm_bwd": "grouped_bwd_kernel",
     "softmax_xent": "softmax_xent_kernel",
-    "sgd_update": "update_kernel", "average": "average_kernel", "restart_mean": "mean_kernel",
+    "sgd_update": "update_kernel",
+    "average": "average_kernel (restart_small_kernel<.., true> when N >= 8 and a replica has fewer "
+               "than 262144 floats)",
+    "restart_mean": "mean_kernel (restart_small_kernel<.., false> when N >= 8 and a replica has "
+                    "fewer than 262144 floats)",
     "lsq_steps": "lsq_steps_staged_kernel (lsq_steps_kernel for shapes it does not take)",
     "mlp2_epoch": "mlp2_epoch_kernel",
 }
@@ -109,29 +115,61 @@ def measured_traffic(workload, kernel):
     return rec.get("traffic_bytes_per_launch")
 
 
-def cpu_baseline(w, inp, budget_s=20.0):
-    """The oracle as it stands, timed on the host cores on a bounded number of iterations."""
-    import oracle
+def measured_counters(workload, kernel):
+    """Matrix-core busy fraction, LDS bank-conflict share and wave occupancy of `kernel` from the
+    committed rocprofv3 --pmc readings (same table and validity rule as measured_traffic)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        table = json.load(open(path))
     except Exception:
-        cores = 1
-    args = dict(model=w.model, dims=w.dims, activation=w.activation, features=inp["features"],
-                targets=inp["targets"], x0=inp["x0"], n_workers=w.n_workers, batch=w.batch,
-                lr=w.lr, interval=w.interval, seed=w.index_seed, bf16=(w.gemm_dtype == "bf16"),
-                momentum=w.momentum, momentum_restart=w.momentum_restart)
-    t0 = time.perf_counter()
-    oracle.run_prsgd(iterations=1, **args)
-    t_one = time.perf_counter() - t0
-    iters = int(max(1, min(w.iterations, budget_s / max(t_one, 1e-6))))
-    t0 = time.perf_counter()
-    oracle.run_prsgd(iterations=iters, **args)
-    dt = time.perf_counter() - t0
-    return {"value": w.n_workers * w.batch * iters / dt, "unit": "samples/s", "cores": int(cores),
-            "kind": "oracle",
-            "sample": "%d iterations of workload %s (incl. %d restart averages), %.1f s, numpy float64"
-                      % (iters, w.name, iters // w.interval, dt)}
+        return None
+    rec = table.get(workload, {}).get(kernel)
+    if not rec or rec.get("source_sha256") != kernel_source_digest():
+        return None
+    return rec.get("counters")
+
+
+def cpu_baseline(w, inp, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores on a bounded number of iterations:
+    once with the BLAS threads numpy starts by itself (all-core figure, `value`) and once
+    restricted to one thread (`single_thread`), the latter on worker 0's share of an iteration
+    when a whole iteration would not fit the budget (workers are independent inside an
+    iteration, so samples/s scales with the share)."""
+    import oracle
+    from threadpoolctl import threadpool_info, threadpool_limits
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    common = dict(model=w.model, dims=w.dims, activation=w.activation, x0=inp["x0"], batch=w.batch,
+                  lr=w.lr, interval=w.interval, seed=w.index_seed, bf16=(w.gemm_dtype == "bf16"),
+                  momentum=w.momentum, momentum_restart=w.momentum_restart)
+    full = dict(common, features=inp["features"], targets=inp["targets"], n_workers=w.n_workers)
+    one = dict(common, features=inp["features"][:1], targets=inp["targets"][:1], n_workers=1)
+
+    def timed(args, iters):
+        t0 = time.perf_counter()
+        oracle.run_prsgd(iterations=iters, **args)
+        return time.perf_counter() - t0
+
+    def sample(args, n_workers, what):
+        t_one = timed(args, 1)                      # also warms the allocator and the BLAS threads
+        iters = int(max(1, min(w.iterations, budget_s / max(t_one, 1e-6))))
+        dt = timed(args, iters)
+        restarts = iters // w.interval
+        note = "%d iterations of %s (incl. %d restart averages), %.1f s, numpy float64" % (
+            iters, what, restarts, dt)
+        if iters < 2 * w.interval:
+            note += "; shorter than two restart intervals: the rate is extrapolated linearly in T " \
+                    "(a restart average is one pass over N*m doubles, far below one iteration's cost)"
+        return n_workers * w.batch * iters / dt, note, t_one
+
+    value, note, t_one = sample(full, w.n_workers, "workload %s" % w.name)
+    out = {"value": value, "unit": "samples/s", "cores": int(cores), "kind": "oracle", "sample": note}
+    with threadpool_limits(limits=1):
+        if t_one * cores <= 2 * budget_s:           # a whole single-threaded iteration fits
+            v1, n1, _ = sample(full, w.n_workers, "workload %s" % w.name)
+        else:
+            v1, n1, _ = sample(one, 1, "worker 0's share (1/%d) of workload %s" % (w.n_workers, w.name))
+    out["single_thread"] = {"value": v1, "unit": "samples/s", "cores": 1, "sample": n1}
+    return out
 
 
 def restart_average_at_hbm_scale(prsgd, drivers, get_workload, make_inputs, reps=20):
@@ -195,7 +233,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c5")
     ap.add_argument("--interval", type=int, default=None)
     ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
     ap.add_argument("--eager-restart", action="store_true",
@@ -254,7 +292,7 @@ def main() -> int:
     if args.momentum_restart is not None:
         w = w.scaled(momentum_restart=args.momentum_restart)
     steps = args.steps if args.steps is not None else min(w.iterations, 2000)
-    warmup = args.warmup if args.warmup is not None else 2 * w.interval
+    warmup = args.warmup if args.warmup is not None else min(2 * w.interval, 32)
 
     inp = make_inputs(w)
     stream = torch.cuda.Stream(device="cuda:0")
@@ -272,11 +310,14 @@ def main() -> int:
     prsgd.prsgd_run(h, steps, w.interval)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    prsgd.prsgd_status(h)                            # raises if any launch of the run gave up
     loss = float(prsgd.prsgd_read_loss(h).mean())
 
     # per-kernel durations: the same steps again with every launch bracketed by HIP events on
     # the library's stream
-    prof_steps = min(steps, max(2 * w.interval, 64))
+    # whole restart intervals, so that every launch of an epoch kernel covers `interval`
+    # iterations like the launches the traffic counters were read on
+    prof_steps = w.interval * max(2, -(-32 // w.interval))
     prsgd.prsgd_set_iteration(h, 0)
     prsgd.prsgd_profile_enable(h, True)
     prsgd.prsgd_run(h, prof_steps, w.interval)
@@ -309,6 +350,16 @@ def main() -> int:
     else:
         roof = {"bound": "mfma", "achieved": kd["TFLOPs"], "peak": peak_tf, "unit": "TFLOP/s",
                 "frac": kd["TFLOPs"] / peak_tf}
+    # matrix-core view of the same kernel: flops / time against the chip's peak, beside the most
+    # the kernel's arithmetic intensity allows at the HBM peak (the products here are skinny:
+    # every replica has private weights and at most 128 minibatch rows)
+    if kd["flops_per_launch"] > 0 and kd["bytes_per_launch"] > 0:
+        ai = kd["flops_per_launch"] / kd["bytes_per_launch"]
+        roof["mfma"] = {"achieved_TFLOPs": kd["TFLOPs"], "peak_TFLOPs": peak_tf,
+                        "frac_of_peak": kd["TFLOPs"] / peak_tf,
+                        "flop_per_byte": ai,
+                        "ceiling_frac_at_hbm_peak": min(1.0, ai * HBM_PEAK_GBPS * 1e9 / (peak_tf * 1e12)),
+                        "busy_counters": measured_counters(w.name, dom)}
     roof.update({"traffic": measured_traffic(w.name, dom), "kernel": dom, "symbol": KERNEL_SYMBOL.get(dom, dom),
                  "avg_launch_us": kd["avg_us"], "launches_timed": kd["launches"],
                  "algorithmic_bytes_per_launch": kd["bytes_per_launch"],
@@ -346,8 +397,9 @@ def main() -> int:
     prsgd.prsgd_destroy(h)
     del h
     torch.cuda.empty_cache()
-    if restart is not None and restart["bytes"] < (1 << 29) and not args.no_hbm_average:
-        # this workload's replicas are cache-resident: also report the kernel at HBM scale
+    if not args.no_hbm_average:
+        # the second half of the metric, whatever the workload: both restart kernels and the
+        # stand-alone update on a replica set far larger than the caches
         out["restart_average_hbm"] = restart_average_at_hbm_scale(prsgd, drivers, get_workload,
                                                                   make_inputs)
         out["sgd_update_hbm"] = standalone_update_at_hbm_scale(prsgd)

@@ -82,7 +82,7 @@ typedef struct {
                                       average of the buffers overwrites them) | _RESET (zeroed)    */
 } prsgd_config;
 
-/* m: scalar parameters of one replica (0 if the config is invalid). */
+/* m, the dimension of x in eq. (1): scalar parameters of one replica (0 if the config is invalid). */
 size_t prsgd_param_count(const prsgd_config* cfg);
 /* Floats per replica in the device layout (m rounded up with alignment padding). */
 size_t prsgd_param_stride(const prsgd_config* cfg);
@@ -122,7 +122,11 @@ int prsgd_local_steps(prsgd_ctx* ctx, int32_t k);
 int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host /* [N] */);
 
 /*
- * Restart: x_i <- (1/N) sum_j x_j for every i (eq. 2); workers summed in ascending order.
+ * Restart: x_i <- (1/N) sum_j x_j for every i (eq. 2), in fp32, in a fixed order: workers are
+ * summed in ascending order, then one division by N.  Small replica sets (N >= 8 and fewer than
+ * 262144 floats per replica) split the workers into four consecutive quarters that are summed in
+ * ascending order each and then added quarter by quarter, ((q0 + q1) + q2) + q3.  Either way the
+ * result is the same from run to run.
  * After the call every worker's point (as seen by prsgd_read_params and by the next local
  * iteration) is the node average.  By default the broadcast is deferred where the kernels
  * support it: the average is written once and the next local iteration, which rewrites every
@@ -160,7 +164,11 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
 int prsgd_read_velocity(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m);
 int prsgd_write_velocity(prsgd_ctx* ctx, int32_t worker, const float* in_host, size_t m);
 
-/* Minibatch loss F_i of each worker at its most recent local iteration, out_host[N]. */
+/*
+ * Minibatch loss F_i(x_i^{t-1}; zeta_i^t) (the stochastic objective of eq. 1, evaluated where
+ * Algorithm 1 observes the gradient) of each worker at its most recent local iteration,
+ * out_host[N].  Synchronises the stream.
+ */
 int prsgd_read_loss(prsgd_ctx* ctx, float* out_host);
 /* Row indices each worker used at its most recent local iteration, out_host[N][B]. */
 int prsgd_read_indices(prsgd_ctx* ctx, int32_t* out_host);
@@ -181,16 +189,37 @@ int prsgd_sgd_update(float* x_dev, const float* g_dev, uint16_t* shadow_dev, siz
                      float lr, void* hip_stream);
 
 /*
- * Measurement aid, not part of the method: a plain device-to-device copy kernel of `bytes`
- * bytes (a multiple of 16; both pointers 16-byte aligned) whose traffic is known exactly.
- * Used to calibrate achievable HBM bandwidth and the fetch/write hardware counters against
- * which the kernels above are compared.
+ * Epoch lengths and learning rates of Algorithm 2 as Theorem 2 chooses them:
+ *   lengths_host[s-1] = K^s = ceil(s^(1/3) / N),   rates_host[s-1] = gamma^s = N / s^(2/3),
+ * s = 1..n_epochs (host arrays of n_epochs elements).  K^s is computed in integer arithmetic
+ * (the smallest k with (k N)^3 >= s).  Algorithm 2 is then: for every epoch prsgd_average,
+ * prsgd_set_lr(gamma^s), prsgd_local_steps(K^s).  PRSGD_EINVAL for a null array or N < 1.
  */
-int prsgd_copy_bytes(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
+int prsgd_time_varying_schedule(int32_t n_epochs, int32_t n_workers, int32_t* lengths_host,
+                                float* rates_host);
 
-int     prsgd_set_lr(prsgd_ctx* ctx, float lr);           /* gamma for later iterations      */
-int     prsgd_set_iteration(prsgd_ctx* ctx, int64_t t);   /* resume: counter of done iterations */
-int64_t prsgd_iteration(const prsgd_ctx* ctx);            /* iterations done so far, <0 on null */
+/*
+ * Learning rate of the iterations that follow: gamma of Algorithm 1, or gamma^s of epoch s of
+ * Algorithm 2 (time-varying rates, Theorem 2) when called between epochs.
+ */
+int     prsgd_set_lr(prsgd_ctx* ctx, float lr);
+/* t of Algorithm 1: iterations done so far (the index stream and the restart phase follow it). */
+int     prsgd_set_iteration(prsgd_ctx* ctx, int64_t t);   /* resume from a checkpoint            */
+int64_t prsgd_iteration(const prsgd_ctx* ctx);            /* < 0 on a null context               */
+
+/*
+ * Synchronises the stream and reports whether every launch so far ran to completion.
+ * One-hidden-layer fp32 MLPs run whole epochs in one launch whose workgroups wait for each other
+ * inside the kernel; that needs all of them resident at once, which holds on a device that runs
+ * nothing else (checked at prsgd_init) -- keep the device otherwise idle while such a context is
+ * stepping.  If other work did hold compute units, the kernel's bounded wait gives up instead of
+ * hanging: this call (like every prsgd_read_* call) then returns PRSGD_ESTATE, the replicas are
+ * inconsistent, and prsgd_local_steps / prsgd_average / prsgd_run keep returning PRSGD_ESTATE
+ * until every replica has been rewritten with prsgd_write_params (worker -1, or each worker
+ * once).  From then on the context runs its local steps as a chain of per-layer kernels, which
+ * needs no co-resident workgroups.
+ */
+int prsgd_status(prsgd_ctx* ctx);
 
 /*
  * Per-kernel timing with HIP events on the context's stream.  While enabled every kernel

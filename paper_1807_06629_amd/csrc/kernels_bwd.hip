@@ -21,9 +21,6 @@
 
 namespace prsgd {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
@@ -38,28 +35,6 @@ constexpr int SG = BN + 4;         // LDS row stride of the dW tile [k][n]  (flo
 #define PRSGD_BWD_STAGES 2
 #endif
 
-// Fragment of an operand whose contraction index is the row index of the LDS tile ([c][row]):
-// LDS transpose load, 4(c) x 16(row) blocks transposed in flight (two loads = 8 contraction
-// elements of the lane's row).
-__device__ __forceinline__ bf16x8_t frag_trans(const uint16_t* lds, int stride, int row_block, int kk,
-                                               int lane) {
-  typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
-  typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
-  const int g = lane >> 4, r = lane & 15;
-  const int c = kk * 16 + 8 * (g >> 1) + (r >> 2);
-  const int row = row_block + 16 * (g & 1) + 4 * (r & 3);
-  const uint16_t* p = lds + c * stride + row;
-  const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
-  const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + 4 * stride));
-  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-// Fragment of an operand stored [row][c]: one 16-byte read.
-__device__ __forceinline__ bf16x8_t frag_contig(const uint16_t* lds, int stride, int row_block, int kk,
-                                                int lane) {
-  const u16x8_t u = *reinterpret_cast<const u16x8_t*>(lds + (row_block + (lane & 31)) * stride + kk * 16 +
-                                                      (lane >> 5) * 8);
-  return __builtin_bit_cast(bf16x8_t, u);
-}
 __device__ __forceinline__ f32x16_t mfma_bf16(bf16x8_t a, bf16x8_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

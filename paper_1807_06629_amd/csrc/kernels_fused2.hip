@@ -24,7 +24,6 @@ namespace prsgd {
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr unsigned kSpinLimit = 1u << 22;     // bounded wait: a lost team member aborts the launch
 constexpr int kTT = 512;                      // threads per team member: two wavefronts per SIMD, so
 constexpr int kTW = kTT / kWave;              // that the latency-bound phases of one overlap the other's
 constexpr int kAgentScope = 16;               // buffer-load cache policy: the sc1 bit (agent scope)
@@ -345,7 +344,7 @@ __global__ __launch_bounds__(kTT) void mlp2_epoch_kernel(Fused2Args p) {
       unsigned spins = 0;
       int bad = 0;
       while ((int)(__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-        if (++spins > kSpinLimit ||
+        if (++spins > p.spin_limit ||
             __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
           __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           bad = 1;
@@ -670,8 +669,9 @@ hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s) {
   args.d2p = pl.d2p;
   args.ldx = pl.ldx;
   void* kargs[] = {&args};
-  // Plain launch: fused2_plan has checked that the whole grid fits on the device at once, and a
-  // team member that never shows up ends in the kernel's bounded wait, not in a hang.
+  // Plain launch: fused2_plan has checked that the whole grid fits on an otherwise idle device at
+  // once, and a team member that never shows up (other work holding compute units) ends in the
+  // kernel's bounded wait and the abort flag, not in a hang.
   return hipLaunchKernel(sym, dim3((unsigned)(args.n_workers * pl.P)), dim3(kTT), kargs,
                          fused2_lds_bytes(pl), s);
 }

@@ -19,10 +19,6 @@
 
 namespace prsgd {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
 enum { OP_CONTIG = 0, OP_TRANS = 1 };
 
 struct TF32 {
@@ -136,31 +132,14 @@ __device__ __forceinline__ float load_frag_f32(const float* __restrict__ lds, in
   if (KIND == OP_CONTIG) return lds[row * TileShape<TF32, ROWS, KIND>::kStride + kk * 2 + kb];
   return lds[(kk * 2 + kb) * TileShape<TF32, ROWS, KIND>::kStride + row];
 }
-// bf16 fragment.  A contraction-contiguous tile gives it in one 16-byte read.  A transposed
-// tile [c][row] is read with the LDS transpose load (ds_read_b64_tr_b16): inside each group of
-// 16 lanes, lane r supplies the address of a 4-element row M[r] and lane i receives
-// M[4j + i/4][i%4], j = 0..3.  Addressing lane r at (c = c0 + r/4, rows 4*(r%4)..+3) therefore
-// hands lane i the four consecutive c of row i: a 4(c) x 16(row) block transposed in flight.
-// Two such loads give the eight contraction elements of the fragment.
+// bf16 fragment: one 16-byte read of a contraction-contiguous tile, the LDS transpose load for a
+// tile stored with the contraction index as its row.
 template <int ROWS, int KIND>
 __device__ __forceinline__ bf16x8_t load_frag_bf16(const uint16_t* __restrict__ lds, int row_block,
                                                    int kk, int lane) {
   constexpr int STRIDE = TileShape<TBF16, ROWS, KIND>::kStride;
-  if (KIND == OP_CONTIG) {
-    const u16x8_t u = *reinterpret_cast<const u16x8_t*>(lds + (row_block + (lane & 31)) * STRIDE +
-                                                        kk * 16 + (lane >> 5) * 8);
-    return __builtin_bit_cast(bf16x8_t, u);
-  } else {
-    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
-    typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
-    const int g = lane >> 4, r = lane & 15;
-    const int c = kk * 16 + 8 * (g >> 1) + (r >> 2);
-    const int row = row_block + 16 * (g & 1) + 4 * (r & 3);
-    const uint16_t* p = lds + c * STRIDE + row;
-    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
-    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + 4 * STRIDE));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  }
+  if (KIND == OP_CONTIG) return frag_contig(lds, STRIDE, row_block, kk, lane);
+  return frag_trans(lds, STRIDE, row_block, kk, lane);
 }
 
 __device__ __forceinline__ f32x16_t mfma(float a, float b, f32x16_t c) {

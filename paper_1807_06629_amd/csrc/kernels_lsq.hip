@@ -277,7 +277,14 @@ hipError_t launch_lsq_steps(const float* features, const float* targets, const f
     STAGED(8, 1);
 #undef STAGED
   }
+  // at most (2 * 8192 + 2 * 4096) floats = 96 KiB: inside the 160 KiB of a compute unit, but
+  // above the default limit of a launch
   const size_t lds_bytes = (2 * (size_t)d + 2 * (size_t)batch) * sizeof(float);
+  if (lds_bytes > 48 * 1024) {
+    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(lsq_steps_kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (ea != hipSuccess) return ea;
+  }
   hipLaunchKernelGGL(lsq_steps_kernel, dim3(n_workers), dim3(kThreads), lds_bytes, s, features, targets,
                      src, src_stride, params, velocity, mu, losses, idx, d, m_pad, rows, ilog2_rows(rows), batch, lr, seed,
                      (uint64_t)t0, k, worker_steps);

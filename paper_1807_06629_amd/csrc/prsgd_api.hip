@@ -9,6 +9,7 @@
 #include <new>
 #include <vector>
 
+#include "prsgd_aux.h"
 #include "prsgd_internal.h"
 
 using namespace prsgd;
@@ -157,6 +158,11 @@ struct prsgd_ctx {
   bool lazy_restart;    // a restart only writes the node average; the next local iteration
                         // reads it as every worker's starting point (no broadcast)
   bool at_mean;         // the replicas are stale: every worker's current point is the vector `mean`
+  bool poisoned;        // the epoch kernel gave up a team barrier: the replicas are inconsistent
+                        // until the caller restores them (prsgd_write_params)
+  std::vector<char> restored;   // workers written since the abort
+  size_t n_restored;
+  unsigned int spin_limit;      // polls of the epoch kernel's team barrier before it gives up
   hipStream_t stream;
   const float* features;
   const void* targets;
@@ -405,6 +411,7 @@ Fused2Args fused2_args(prsgd_ctx* ctx, int k, const int* worker_steps) {
   a.worker_steps = worker_steps;
   a.part = ctx->at<float>(ctx->cv.part);
   a.sync = ctx->at<unsigned int>(ctx->cv.sync);
+  a.spin_limit = ctx->spin_limit;
   a.row_loss = ctx->at<float>(ctx->cv.row_loss);
   a.idx = ctx->at<int32_t>(ctx->cv.idx);
   a.vel = ctx->velocity();
@@ -412,17 +419,39 @@ Fused2Args fused2_args(prsgd_ctx* ctx, int k, const int* worker_steps) {
   return a;
 }
 
-// The epoch kernel's bounded team barrier raises a flag instead of hanging; surface it.
+constexpr const char* kPoisonedMsg =
+    "the epoch kernel gave up waiting for a team member (was other work running on the device?); "
+    "the replicas are inconsistent: restore them with prsgd_write_params (and prsgd_set_iteration)";
+
+// Calls that enqueue work refuse to run on replicas an aborted epoch launch left inconsistent.
+int check_poisoned(prsgd_ctx* ctx) {
+  return ctx->poisoned ? set_err(ctx, PRSGD_ESTATE, "%s", kPoisonedMsg) : PRSGD_OK;
+}
+
+// The epoch kernel's bounded team barrier raises a flag instead of hanging.  Called wherever the
+// stream is synchronised anyway: reads the flag (4 bytes); if it is set, clears it, marks the
+// context poisoned and switches every later local step to the per-layer kernel chain, which needs
+// no co-resident workgroups.
 int check_fused2_abort(prsgd_ctx* ctx) {
+  if (ctx->poisoned) return set_err(ctx, PRSGD_ESTATE, "%s", kPoisonedMsg);
   if (!ctx->use_fused2) return PRSGD_OK;
+  unsigned int* flag_dev = ctx->at<unsigned int>(ctx->cv.sync) + (size_t)ctx->cfg.n_workers * 32;
   unsigned int flag = 0;
-  hipError_t e = hipMemcpyAsync(&flag, ctx->at<unsigned int>(ctx->cv.sync) + (size_t)ctx->cfg.n_workers * 32,
-                                sizeof(flag), hipMemcpyDeviceToHost, ctx->stream);
+  hipError_t e = hipMemcpyAsync(&flag, flag_dev, sizeof(flag), hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "abort-flag read");
-  if (flag != 0)
-    return set_err(ctx, PRSGD_ESTATE, "epoch kernel gave up waiting for a team member; parameters are invalid");
-  return PRSGD_OK;
+  if (flag == 0) return PRSGD_OK;
+  const unsigned int zero = 0;
+  e = hipMemcpyAsync(flag_dev, &zero, sizeof(zero), hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "abort-flag reset");
+  ctx->use_fused2 = false;
+  if (ctx->cfg.momentum != 0.0f) ctx->cfg.fused_update = 0;   // the chain applies momentum elementwise
+  ctx->poisoned = true;
+  ctx->at_mean = false;
+  ctx->n_restored = 0;
+  ctx->restored.assign((size_t)ctx->cfg.n_workers, 0);
+  return set_err(ctx, PRSGD_ESTATE, "%s", kPoisonedMsg);
 }
 
 // Writes the node average into every replica (and the bf16 shadow) if the last restart left the
@@ -522,6 +551,9 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   ctx->t = 0;
   ctx->lazy_restart = true;
   ctx->at_mean = false;
+  ctx->poisoned = false;
+  ctx->n_restored = 0;
+  ctx->spin_limit = kFused2SpinLimit;
   ctx->lr = cfg->lr;
   ctx->err[0] = 0;
   ctx->profiling = false;
@@ -530,6 +562,7 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
   try {
     ctx->host_pad.resize((size_t)lo.m_pad);
+    ctx->restored.assign((size_t)cfg->n_workers, 0);
   } catch (...) {
     delete ctx;
     return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
@@ -558,6 +591,7 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
 int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (k < 0) return set_err(ctx, PRSGD_EINVAL, "k must be >= 0");
+  if (check_poisoned(ctx) != PRSGD_OK) return PRSGD_ESTATE;
   const prsgd_config& c = ctx->cfg;
   if (c.model == PRSGD_LSQ) {
     if (k == 0) return PRSGD_OK;
@@ -592,6 +626,7 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
   if (steps_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "steps_host is null");
   if (ctx->cfg.momentum != 0.0f)
     return set_err(ctx, PRSGD_EINVAL, "heterogeneous epochs are not defined with momentum");
+  if (check_poisoned(ctx) != PRSGD_OK) return PRSGD_ESTATE;
   const prsgd_config& c = ctx->cfg;
   int32_t k_max = 0;
   for (int i = 0; i < c.n_workers; ++i) {
@@ -633,6 +668,7 @@ int prsgd_local_steps_hetero(prsgd_ctx* ctx, const int32_t* steps_host) {
 
 int prsgd_average(prsgd_ctx* ctx) {
   if (ctx == nullptr) return PRSGD_EINVAL;
+  if (check_poisoned(ctx) != PRSGD_OK) return PRSGD_ESTATE;
   if (ctx->at_mean) return PRSGD_OK;        // all workers already sit at their node average
   if (ctx->velocity() != nullptr && ctx->cfg.momentum_restart != PRSGD_MOM_KEEP) {
     // the paper leaves the momentum buffers at a restart open: average them like the points,
@@ -721,6 +757,14 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
     const int mrc = materialize(ctx);
     if (mrc != PRSGD_OK) return mrc;
   }
+  if (ctx->poisoned) {                      // an aborted epoch launch: usable again once every
+    if (worker < 0) {                       // replica has been rewritten
+      ctx->poisoned = false;
+    } else if (!ctx->restored[(size_t)worker]) {
+      ctx->restored[(size_t)worker] = 1;
+      if (++ctx->n_restored == (size_t)ctx->cfg.n_workers) ctx->poisoned = false;
+    }
+  }
   ctx->at_mean = false;
   pad_from_dense(ctx, in_host, ctx->host_pad.data());
   const size_t bytes = sizeof(float) * (size_t)ctx->lo.m_pad;
@@ -749,6 +793,8 @@ int prsgd_read_velocity(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t 
   if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
   if (worker < 0 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
   if (ctx->velocity() == nullptr) return set_err(ctx, PRSGD_ESTATE, "the context has no momentum buffers");
+  const int arc = check_fused2_abort(ctx);
+  if (arc != PRSGD_OK) return arc;
   hipError_t e = hipMemcpyAsync(ctx->host_pad.data(), ctx->velocity() + (size_t)worker * ctx->lo.m_pad,
                                 sizeof(float) * (size_t)ctx->lo.m_pad, hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
@@ -774,6 +820,8 @@ int prsgd_write_velocity(prsgd_ctx* ctx, int32_t worker, const float* in_host, s
 int prsgd_read_loss(prsgd_ctx* ctx, float* out_host) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
+  const int arc = check_fused2_abort(ctx);
+  if (arc != PRSGD_OK) return arc;
   hipError_t e = hipSuccess;
   if (ctx->cfg.model == PRSGD_MLP)
     e = launch_loss_mean(ctx->at<float>(ctx->cv.row_loss), ctx->at<float>(ctx->cv.losses),
@@ -789,6 +837,8 @@ int prsgd_read_loss(prsgd_ctx* ctx, float* out_host) {
 int prsgd_read_indices(prsgd_ctx* ctx, int32_t* out_host) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (out_host == nullptr) return set_err(ctx, PRSGD_EINVAL, "out_host is null");
+  const int arc = check_fused2_abort(ctx);
+  if (arc != PRSGD_OK) return arc;
   const size_t bytes = sizeof(int32_t) * (size_t)ctx->cfg.n_workers * ctx->cfg.batch;
   hipError_t e = hipMemcpyAsync(out_host, ctx->at<int32_t>(ctx->cv.idx), bytes, hipMemcpyDeviceToHost,
                                 ctx->stream);
@@ -825,6 +875,38 @@ int prsgd_copy_bytes(void* dst_dev, const void* src_dev, size_t bytes, void* hip
     return set_err(nullptr, PRSGD_EINVAL, "prsgd_copy_bytes: bad argument");
   hipError_t e = launch_copy(dst_dev, src_dev, bytes, reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return hip_fail(nullptr, e, "prsgd_copy_bytes");
+  return PRSGD_OK;
+}
+
+int prsgd_status(prsgd_ctx* ctx) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  const int arc = check_fused2_abort(ctx);
+  if (arc != PRSGD_OK) return arc;
+  const hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_status");
+  return PRSGD_OK;
+}
+
+int prsgd_set_epoch_wait_limit(prsgd_ctx* ctx, uint32_t polls) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  ctx->spin_limit = polls;
+  return PRSGD_OK;
+}
+
+int prsgd_time_varying_schedule(int32_t n_epochs, int32_t n_workers, int32_t* lengths_host,
+                                float* rates_host) {
+  if (n_epochs < 0 || n_workers < 1 || (n_epochs > 0 && (lengths_host == nullptr || rates_host == nullptr)))
+    return set_err(nullptr, PRSGD_EINVAL, "prsgd_time_varying_schedule: bad argument");
+  // K^s = ceil(s^(1/3) / N) is the smallest integer k with (k N)^3 >= s: integer arithmetic, so
+  // that perfect cubes land exactly.  k N only ever grows with s.
+  unsigned __int128 kn = (unsigned __int128)n_workers;      // current k N
+  int32_t k = 1;
+  for (int32_t s = 1; s <= n_epochs; ++s) {
+    while (kn * kn * kn < (unsigned __int128)s) { kn += (unsigned __int128)n_workers; ++k; }
+    lengths_host[s - 1] = k;
+    const double c = cbrt((double)s);
+    rates_host[s - 1] = (float)((double)n_workers / (c * c));
+  }
   return PRSGD_OK;
 }
 

@@ -109,9 +109,11 @@ struct Fused2Args {
   const int* worker_steps;       // Algorithm 3 step counts (nullptr: every worker takes k steps)
   float* part;                   // [2][N][P][MT*16][d2p] partial logits
   unsigned int* sync;            // [N][32] arrival counters (+ launch base), then the abort flag
+  unsigned int spin_limit;       // polls of the team barrier before a member gives up
   float* row_loss; int32_t* idx;
   float* vel; float mu;          // momentum buffers [N][m_pad] (nullptr = plain SGD)
 };
+constexpr unsigned int kFused2SpinLimit = 1u << 22;   // default bound of the team barrier's wait
 size_t fused2_lds_bytes(const Fused2Plan& pl);
 bool fused2_plan(int n_workers, int d0, int d1, int d2, int batch, bool momentum, Fused2Plan* pl);
 hipError_t launch_fused2(const Fused2Plan& pl, Fused2Args args, hipStream_t s);
@@ -160,11 +162,46 @@ hipError_t launch_lsq_steps(const float* features, const float* targets, const f
 // ---- small device helpers ------------------------------------------------------------------
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
+  // a NaN stays a NaN (quiet bit set): adding the rounding bias would carry some NaN patterns
+  // into the exponent and turn them into infinity or zero
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
   u += 0x7FFFu + ((u >> 16) & 1u);          // round to nearest, ties to even
   return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) {
   return __uint_as_float(((uint32_t)h) << 16);
+}
+
+// ---- bf16 MFMA operand fragments out of LDS ----------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// Fragment of lane (r = lane % 32, kb = lane / 32) for the kk-th 16-deep contraction slice of a
+// tile stored [row][c] (contraction index contiguous): one 16-byte read.
+__device__ __forceinline__ bf16x8_t frag_contig(const uint16_t* lds, int stride, int row_block, int kk,
+                                                int lane) {
+  const u16x8_t u = *reinterpret_cast<const u16x8_t*>(lds + (row_block + (lane & 31)) * stride + kk * 16 +
+                                                      (lane >> 5) * 8);
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+// The same fragment of a tile stored [c][row] (contraction index is the LDS row), read with the
+// LDS transpose load (ds_read_b64_tr_b16): inside each group of 16 lanes, lane r supplies the
+// address of a 4-element row M[r] and lane i receives M[4j + i/4][i%4], j = 0..3.  Addressing
+// lane r at (c = c0 + r/4, rows 4*(r%4)..+3) therefore hands lane i the four consecutive c of
+// row i: a 4(c) x 16(row) block transposed in flight.  Two such loads give the eight contraction
+// elements of the fragment.
+__device__ __forceinline__ bf16x8_t frag_trans(const uint16_t* lds, int stride, int row_block, int kk,
+                                               int lane) {
+  typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+  typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
+  const int g = lane >> 4, r = lane & 15;
+  const int c = kk * 16 + 8 * (g >> 1) + (r >> 2);
+  const int row = row_block + 16 * (g & 1) + 4 * (r & 3);
+  const uint16_t* p = lds + c * stride + row;
+  const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
+  const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + 4 * stride));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies

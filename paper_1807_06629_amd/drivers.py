@@ -1,7 +1,6 @@
 """Host loops of the paper's algorithms on top of the C-ABI calls (no arithmetic here)."""
 from __future__ import annotations
 
-import math
 from typing import Dict, Sequence
 
 import numpy as np
@@ -30,11 +29,9 @@ def run_algorithm1(h: prsgd.Handle, iterations: int, interval: int) -> None:
 
 
 def time_varying_schedule(n_epochs: int, n_workers: int):
-    """Theorem 2: K^s = ceil(s^(1/3) / N) and gamma^s = N / s^(2/3) for s = 1..S."""
-    lengths = [max(1, math.ceil(round(s ** (1.0 / 3.0), 12) / n_workers)) for s in
-               range(1, n_epochs + 1)]
-    rates = [n_workers / s ** (2.0 / 3.0) for s in range(1, n_epochs + 1)]
-    return lengths, rates
+    """Theorem 2's epoch lengths K^s and rates gamma^s, s = 1..S, as the library computes them."""
+    ks, gs = prsgd.prsgd_time_varying_schedule(n_epochs, n_workers)
+    return [int(k) for k in ks], [float(g) for g in gs]
 
 
 def run_algorithm2(h: prsgd.Handle, epoch_lengths: Sequence[int], epoch_rates: Sequence[float]) -> None:

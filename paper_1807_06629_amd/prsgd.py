@@ -1,6 +1,7 @@
 """Thin ctypes binding of libprsgd (argument marshalling only).
 
-Every function mirrors one entry point of include/prsgd.h under the same name.  PyTorch is
+Every function mirrors one entry point of include/prsgd.h (or include/prsgd_aux.h, the
+measurement and test aids) under the same name.  PyTorch is
 used for device memory (the replica buffer and the workspace are torch tensors) and for the
 HIP stream; all arithmetic of the method runs in the library's kernels.  There is no CPU
 fallback: importing this module without a built libprsgd.so raises.
@@ -80,6 +81,9 @@ def _load() -> ctypes.CDLL:
         "prsgd_sample_indices": (ctypes.c_int, [ctypes.c_uint64, i32, i32, i64, i64, i32, vp, vp]),
         "prsgd_sgd_update": (ctypes.c_int, [vp, vp, vp, sz, ctypes.c_float, vp]),
         "prsgd_copy_bytes": (ctypes.c_int, [vp, vp, sz, vp]),
+        "prsgd_time_varying_schedule": (ctypes.c_int, [i32, i32, vp, vp]),
+        "prsgd_status": (ctypes.c_int, [vp]),
+        "prsgd_set_epoch_wait_limit": (ctypes.c_int, [vp, ctypes.c_uint32]),
         "prsgd_set_lr": (ctypes.c_int, [vp, ctypes.c_float]),
         "prsgd_set_iteration": (ctypes.c_int, [vp, i64]),
         "prsgd_iteration": (i64, [vp]),
@@ -286,6 +290,22 @@ def prsgd_copy_bytes(dst: torch.Tensor, src: torch.Tensor) -> None:
     with torch.cuda.device(src.device):
         s = torch.cuda.current_stream(src.device)
         _check(_lib.prsgd_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(s)))
+
+
+def prsgd_time_varying_schedule(n_epochs: int, n_workers: int):
+    """(K^s, gamma^s) for s = 1..n_epochs as int32 / float32 arrays."""
+    ks = np.empty(max(n_epochs, 0), dtype=np.int32)
+    gs = np.empty(max(n_epochs, 0), dtype=np.float32)
+    _check(_lib.prsgd_time_varying_schedule(int(n_epochs), int(n_workers), ks.ctypes.data, gs.ctypes.data))
+    return ks, gs
+
+
+def prsgd_status(h: Handle) -> None:
+    _check(_lib.prsgd_status(h.ctx), h.ctx)
+
+
+def prsgd_set_epoch_wait_limit(h: Handle, polls: int) -> None:
+    _check(_lib.prsgd_set_epoch_wait_limit(h.ctx, int(polls)), h.ctx)
 
 
 def prsgd_set_lr(h: Handle, lr: float) -> None:

@@ -20,9 +20,15 @@ def P():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "prsgd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(prsgd_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(prsgd_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(P):
@@ -86,8 +92,31 @@ def test_null_context_calls_return_einval(P):
     assert P._lib.prsgd_destroy(None) == P.PRSGD_EINVAL
 
 
-def test_theorem2_schedule_of_the_driver():
-    from paper_1807_06629_amd.drivers import time_varying_schedule
-    ks, gs = time_varying_schedule(27, 2)
+def test_theorem2_schedule_of_the_library(P):
+    ks, gs = P.prsgd_time_varying_schedule(27, 2)
     assert ks[0] == 1 and ks[7] == 1 and ks[26] == 2
     assert gs[0] == 2.0 and gs[7] == pytest.approx(0.5)
+    assert P._lib.prsgd_time_varying_schedule(3, 0, None, None) == P.PRSGD_EINVAL
+    assert P._lib.prsgd_time_varying_schedule(3, 1, None, None) == P.PRSGD_EINVAL
+    assert len(P.prsgd_time_varying_schedule(0, 4)[0]) == 0
+
+
+@pytest.mark.parametrize("n_workers", [1, 2, 8])
+def test_theorem2_schedule_matches_the_oracle_and_the_integer_definition(P, n_workers):
+    # K^s = ceil(s^(1/3) / N): the smallest integer k with (k N)^3 >= s, checked in exact integer
+    # arithmetic, against the oracle's floating-point form and against the library
+    import numpy as np
+    import oracle
+    S = 10000
+    ks, gs = P.prsgd_time_varying_schedule(S, n_workers)
+    oks, ogs = oracle.time_varying_schedule(S, n_workers)
+    for s in range(1, S + 1):
+        k = int(ks[s - 1])
+        assert (k * n_workers) ** 3 >= s and (k == 1 or ((k - 1) * n_workers) ** 3 < s), s
+        assert oks[s - 1] == k, s
+    assert np.allclose(gs, np.asarray(ogs), rtol=2e-7, atol=0)
+    # perfect cubes are where a rounded cube root would be off by one
+    for r in (2, 3, 5, 10, 21):
+        s = (r * n_workers) ** 3
+        if s <= S:
+            assert ks[s - 1] == r and (s == S or ks[s] == r + 1)

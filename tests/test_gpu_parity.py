@@ -90,7 +90,8 @@ def test_c1_least_squares_full_run(P, D):
 # the shapes with d % 4 == 0 and at most 8192 minibatch floats take the LDS-staged kernel in each
 # of its four (vectors per thread, prefetch depth) variants; the others the plain kernel
 @pytest.mark.parametrize("d,batch", [(1, 1), (7, 3), (300, 70), (1000, 9), (4, 1), (32, 40), (128, 20),
-                                     (64, 100), (8, 300), (2048, 4), (16, 512)])
+                                     (64, 100), (8, 300), (2048, 4), (16, 512),
+                                     (8192, 2), (8192, 600)])   # largest d: > 64 KiB of LDS in the plain kernel
 def test_least_squares_ragged_shapes(P, D, d, batch):
     w = get_workload("c1").scaled(dims=(d,), batch=batch, rows_per_worker=128, n_workers=3,
                                   lr=0.01 / max(1, d // 64), interval=3, iterations=10)
@@ -373,6 +374,45 @@ def test_restart_average_properties(P, D, n_workers):
     P.prsgd_destroy(h)
 
 
+@pytest.mark.parametrize("name", ["c3", "c5"])
+def test_eager_average_at_full_replica_sets(P, D, name):
+    # the replica sets of the two bf16 configurations (269 MB / 1.74 GB of fp32 masters) select the
+    # two-column averaging kernel, cached (c3) and streaming (c5); random replicas, the stand-alone
+    # average + broadcast kernel, against the oracle's node average
+    w = get_workload(name).scaled(rows_per_worker=64, batch=8)
+    inp = make_inputs(w)
+    h = _open(D, w, inp)
+    P.prsgd_set_lazy_restart(h, False)
+    rng = np.random.default_rng(5)
+    xs = rng.standard_normal((w.n_workers, h.m), dtype=np.float32)
+    for i in range(w.n_workers):
+        P.prsgd_write_params(h, i, xs[i])
+    P.prsgd_profile_enable(h, True)
+    P.prsgd_average(h)
+    names = {r["name"] for r in P.prsgd_profile_read(h)}
+    P.prsgd_profile_enable(h, False)
+    assert names == {"average"}
+    want = oracle.node_average(xs.astype(np.float64))
+    bound = 2e-7 * w.n_workers * np.abs(xs).max()
+    for i in (0, w.n_workers // 2, w.n_workers - 1):
+        got = P.prsgd_read_params(h, i)
+        assert np.abs(got - want).max() <= bound
+        if i == 0:
+            first = got
+        else:
+            assert np.array_equal(got, first)                # replicas bit-equal after a restart
+    # the bf16 image every replica carries is the rounded mean: one more local step from it equals
+    # a step of a context initialised at the mean
+    P.prsgd_local_steps(h, 1)
+    after = P.prsgd_read_params(h, w.n_workers - 1)
+    P.prsgd_destroy(h)
+    w2 = w
+    h2 = D.open_workload(w2, dict(inp, x0=first), device="cuda:0")
+    P.prsgd_local_steps(h2, 1)
+    assert np.array_equal(P.prsgd_read_params(h2, w.n_workers - 1), after)
+    P.prsgd_destroy(h2)
+
+
 LAZY_CASES = [
     ("lsq", dict()),
     ("epoch", dict(dims=(64, 32, 10), batch=8, n_workers=3)),
@@ -649,19 +689,43 @@ def test_momentum_checkpoint_resume_and_errors(P, D):
 
 
 # --------------------------------------------------------------------------- stand-alone update
-@pytest.mark.parametrize("count", [4, 1000, 4099, 1 << 20])
+# 2^26 and 2^28 elements select the streaming (non-temporal) variant of the kernel
+@pytest.mark.parametrize("count", [4, 1000, 4099, 1 << 20, (1 << 26) + 3, 1 << 28])
 def test_standalone_sgd_update(P, count):
-    rng = np.random.default_rng(count)
-    x = rng.standard_normal(count).astype(np.float32)
-    g = rng.standard_normal(count).astype(np.float32)
+    rng = np.random.default_rng(count % 1000003)
+    x = rng.standard_normal(count, dtype=np.float32)
+    g = rng.standard_normal(count, dtype=np.float32)
     xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda()
     sh = torch.zeros(count, dtype=torch.bfloat16, device="cuda")
     P.prsgd_sgd_update(xd, gd, 0.05, shadow=sh)
     torch.cuda.synchronize()
-    want = x.astype(np.float64) - np.float64(np.float32(0.05)) * g.astype(np.float64)
     got = xd.cpu().numpy()
-    assert np.abs(got - want).max() <= 1e-7 * np.abs(want).max()
-    assert np.array_equal(sh.float().cpu().numpy(), oracle.round_bf16(got).astype(np.float32))
+    got_sh = sh.float().cpu().numpy()
+    del xd, gd, sh
+    # eq. (3) in float64 on the same float32 inputs; the kernel rounds once (fused multiply-add)
+    lr = np.float64(np.float32(0.05))
+    block = 1 << 24                                     # bounded host memory at the large counts
+    for lo in range(0, count, block):
+        hi = min(count, lo + block)
+        want = x[lo:hi].astype(np.float64) - lr * g[lo:hi].astype(np.float64)
+        assert np.abs(got[lo:hi] - want).max() <= 1e-7 * max(1.0, np.abs(want).max())
+        assert np.array_equal(got_sh[lo:hi], oracle.round_bf16(got[lo:hi]).astype(np.float32))
+
+
+def test_bf16_shadow_keeps_nan_and_infinity(P):
+    # a diverged master must not read as a finite weight in its bf16 image
+    pats = np.array([0x7F800001, 0x7FFFFFFF, 0xFFFFFFFF, 0x7FC00000, 0x7F800000, 0xFF800000,
+                     0x7F7FFFFF, 0x3F808000], dtype=np.uint32).view(np.float32)
+    xd = torch.from_numpy(pats.copy()).cuda()
+    gd = torch.zeros(pats.size, dtype=torch.float32, device="cuda")
+    sh = torch.zeros(pats.size, dtype=torch.bfloat16, device="cuda")
+    P.prsgd_sgd_update(xd, gd, 0.0, shadow=sh)
+    torch.cuda.synchronize()
+    got = sh.float().cpu().numpy()
+    want = oracle.round_bf16(pats).astype(np.float32)
+    assert np.all(np.isnan(got[:4])) and np.all(np.isnan(want[:4]))
+    assert np.array_equal(got[4:], want[4:])
+    assert got[6] == np.inf                              # the largest float rounds up to infinity
 
 
 # --------------------------------------------------------------------------- errors with a live context
@@ -679,4 +743,37 @@ def test_argument_errors_leave_the_context_usable(P, D):
     P.prsgd_local_steps(h, 0)
     assert P.prsgd_iteration(h) == 0
     assert np.array_equal(P.prsgd_read_params(h, 0), inp["x0"])
+    P.prsgd_destroy(h)
+
+
+# --------------------------------------------------------------------------- epoch kernel: the give-up path
+def test_epoch_kernel_give_up_is_reported_and_the_context_falls_back(P, D):
+    # Driven from the host: with a wait limit of zero polls the first team member to reach the
+    # team barrier gives up at once.  Every kernel still runs to its end.
+    w = small_mlp(dims=(64, 32, 10), batch=8, n_workers=8, rows_per_worker=128, interval=4, iterations=10,
+                  activation="tanh")
+    inp = inputs_for(w)
+    h = _open(D, w, inp)
+    P.prsgd_local_steps(h, 2)
+    P.prsgd_status(h)                                     # nothing gave up
+    good = D.read_all(h)
+    P.prsgd_set_epoch_wait_limit(h, 0)
+    P.prsgd_local_steps(h, 4)                             # asynchronous: returns before the kernel ends
+    with pytest.raises(P.PrsgdError) as err:
+        P.prsgd_status(h)
+    assert err.value.code == P.PRSGD_ESTATE and "gave up" in str(err.value)
+    for call in (lambda: P.prsgd_local_steps(h, 1), lambda: P.prsgd_average(h), lambda: P.prsgd_run(h, 2, 2),
+                 lambda: P.prsgd_read_params(h, 0), lambda: P.prsgd_read_loss(h), lambda: P.prsgd_status(h)):
+        with pytest.raises(P.PrsgdError) as err:
+            call()
+        assert err.value.code == P.PRSGD_ESTATE
+    # restore the last good state; the context is usable again and runs the per-layer chain
+    for i in range(w.n_workers):
+        P.prsgd_write_params(h, i, good[i])
+    P.prsgd_set_iteration(h, 2)
+    P.prsgd_status(h)
+    names = _kernel_names(P, h, w.iterations - 2, w.interval)
+    assert "gemm_fwd" in names and "mlp2_epoch" not in names, names
+    want = oracle_run(w, inp)
+    assert rel_err(D.read_all(h), want["x"]) <= 1e-4
     P.prsgd_destroy(h)
