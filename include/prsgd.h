@@ -105,6 +105,25 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
                prsgd_ctx** out_ctx);
 
 /*
+ * prsgd_init for callers that cannot allocate device memory (code under HIP graph capture,
+ * serving loops, harnesses that forbid it): the same context, but its workspace is a static
+ * array inside the library, PRSGD_STATIC_WORKSPACE_BYTES per device, held by every device the
+ * library runs on until the process ends.  The call itself allocates nothing, neither on the
+ * device nor on the host (the context and its staging buffer live in static storage too); the
+ * caller still passes the shards and the replica buffer.  A configuration whose
+ * prsgd_workspace_bytes exceeds the limit is refused with PRSGD_EINVAL (the limit covers the
+ * small, latency-bound configurations: c1, c2, c4); device indices 0..7.  All static contexts of a
+ * device share the one array, so only one may be live per device at a time: a second call before
+ * prsgd_destroy returns PRSGD_ESTATE.  The array keeps what the previous context left in it;
+ * the call clears what the new one needs.  Everything else (errors, stream, ownership) as
+ * prsgd_init.
+ */
+#define PRSGD_STATIC_WORKSPACE_BYTES (16u << 20)
+int prsgd_init_static(const prsgd_config* cfg, const float* x0_host, const void* features_dev,
+                      const void* targets_dev, void* params_dev, void* hip_stream,
+                      prsgd_ctx** out_ctx);
+
+/*
  * k >= 0 iterations of eq. (3) on every worker.  At iteration t (counted from 1) worker i
  * draws B rows of its shard uniformly with replacement: slot j uses word (j mod 4) of
  * Philox4x32-10 with counter (j / 4, t mod 2^32, t >> 32, i) and key (seed mod 2^32,

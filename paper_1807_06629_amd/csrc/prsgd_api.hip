@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -160,7 +161,7 @@ struct prsgd_ctx {
   bool at_mean;         // the replicas are stale: every worker's current point is the vector `mean`
   bool poisoned;        // the epoch kernel gave up a team barrier: the replicas are inconsistent
                         // until the caller restores them (prsgd_write_params)
-  std::vector<char> restored;   // workers written since the abort
+  unsigned char restored[65536 / 8];   // bit i: worker i written since the abort
   size_t n_restored;
   unsigned int spin_limit;      // polls of the epoch kernel's team barrier before it gives up
   hipStream_t stream;
@@ -178,7 +179,10 @@ struct prsgd_ctx {
   double prof_ms[KK_COUNT];
   int64_t prof_n[KK_COUNT];
   // scratch host buffer for padded <-> dense parameter conversion
-  std::vector<float> host_pad;
+  float* host_pad;                    // [m_pad]
+  std::vector<float> host_pad_heap;   // owns it, unless the context lives in static storage
+  int static_slot;                    // >= 0: context, workspace and host_pad are the per-device
+                                      // static ones of prsgd_init_static
 
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   uint16_t* shadow() const { return bf16 ? at<uint16_t>(cv.shadow) : nullptr; }
@@ -450,7 +454,7 @@ int check_fused2_abort(prsgd_ctx* ctx) {
   ctx->poisoned = true;
   ctx->at_mean = false;
   ctx->n_restored = 0;
-  ctx->restored.assign((size_t)ctx->cfg.n_workers, 0);
+  memset(ctx->restored, 0, sizeof(ctx->restored));
   return set_err(ctx, PRSGD_ESTATE, "%s", kPoisonedMsg);
 }
 
@@ -516,11 +520,40 @@ size_t prsgd_workspace_bytes(const prsgd_config* cfg) {
   return cv.total;
 }
 
-int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* features_dev,
-               const void* targets_dev, void* params_dev, void* workspace_dev, void* hip_stream,
-               prsgd_ctx** out_ctx) {
-  if (out_ctx == nullptr) return set_err(nullptr, PRSGD_EINVAL, "out_ctx is null");
-  *out_ctx = nullptr;
+}  // extern "C"
+
+namespace {
+
+// Workspace of prsgd_init_static: one array per device, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels and memsets get the
+// device address resolved once per device below.
+constexpr size_t kStaticBytes = PRSGD_STATIC_WORKSPACE_BYTES;
+constexpr int kMaxStaticDevices = 8;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+struct StaticSlot {
+  void* ws_dev = nullptr;             // device address of `scratch` on this device
+  bool in_use = false;
+  alignas(prsgd_ctx) unsigned char ctx_mem[sizeof(prsgd_ctx)];
+};
+StaticSlot g_static[kMaxStaticDevices];
+float g_static_pad[kMaxStaticDevices][kStaticBytes / sizeof(float)];   // host staging, per device
+std::mutex g_static_mutex;
+
+void release_ctx(prsgd_ctx* ctx) {
+  if (ctx->static_slot < 0) { delete ctx; return; }
+  const int slot = ctx->static_slot;
+  ctx->~prsgd_ctx();
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  g_static[slot].in_use = false;
+}
+
+// Shared body of prsgd_init and prsgd_init_static.  static_slot < 0: the context goes on the heap
+// and `workspace_dev` is the caller's; otherwise context, staging buffer and workspace are the
+// slot's static ones and nothing is allocated.
+int init_common(const prsgd_config* cfg, const float* x0_host, const void* features_dev,
+                const void* targets_dev, void* params_dev, void* workspace_dev, void* hip_stream,
+                int static_slot, prsgd_ctx** out_ctx) {
   Layout lo;
   char err[128];
   if (!build_layout(cfg, &lo, err, sizeof(err))) return set_err(nullptr, PRSGD_EINVAL, "%s", err);
@@ -532,8 +565,20 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   if (((uintptr_t)features_dev % 16) != 0 || ((uintptr_t)targets_dev % 4) != 0)
     return set_err(nullptr, PRSGD_EINVAL, "features_dev must be 16-byte and targets_dev 4-byte aligned");
 
-  prsgd_ctx* ctx = new (std::nothrow) prsgd_ctx();
-  if (ctx == nullptr) return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
+  prsgd_ctx* ctx;
+  if (static_slot < 0) {
+    ctx = new (std::nothrow) prsgd_ctx();
+    if (ctx == nullptr) return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
+  } else {
+    // claim the device's slot; from here on every failure path gives it back (release_ctx)
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static[static_slot].in_use)
+      return set_err(nullptr, PRSGD_ESTATE, "prsgd_init_static: the device's static workspace already "
+                                            "serves a live context; destroy it first");
+    g_static[static_slot].in_use = true;
+    ctx = new (g_static[static_slot].ctx_mem) prsgd_ctx();
+  }
+  ctx->static_slot = static_slot;
   ctx->cfg = effective_config(cfg);
   ctx->lo = lo;
   build_carve(cfg, lo, &ctx->cv);
@@ -553,6 +598,7 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   ctx->at_mean = false;
   ctx->poisoned = false;
   ctx->n_restored = 0;
+  memset(ctx->restored, 0, sizeof(ctx->restored));
   ctx->spin_limit = kFused2SpinLimit;
   ctx->lr = cfg->lr;
   ctx->err[0] = 0;
@@ -560,19 +606,25 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   ctx->pool_used = 0;
   memset(ctx->prof_ms, 0, sizeof(ctx->prof_ms));
   memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
-  try {
-    ctx->host_pad.resize((size_t)lo.m_pad);
-    ctx->restored.assign((size_t)cfg->n_workers, 0);
-  } catch (...) {
-    delete ctx;
-    return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
+  if (static_slot >= 0) {
+    ctx->host_pad = g_static_pad[static_slot];       // m_pad floats fit: the workspace holds as many
+  } else {
+    try {
+      ctx->host_pad_heap.resize((size_t)lo.m_pad);
+    } catch (...) {
+      release_ctx(ctx);
+      return set_err(nullptr, PRSGD_ENOMEM, "out of host memory");
+    }
+    ctx->host_pad = ctx->host_pad_heap.data();
   }
 
-  // Zero the workspace once: padding columns of every activation buffer must read as zero.
+  // Zero the workspace once: padding columns of every activation buffer must read as zero, and
+  // the epoch kernel's arrival counters and abort flag start at zero (the static workspace keeps
+  // what the previous context left in it).
   hipError_t e = hipMemsetAsync(ctx->ws, 0, ctx->cv.total, ctx->stream);
   if (e == hipSuccess) {
-    pad_from_dense(ctx, x0_host, ctx->host_pad.data());
-    e = hipMemcpyAsync(ctx->at<float>(ctx->cv.mean), ctx->host_pad.data(), sizeof(float) * (size_t)lo.m_pad,
+    pad_from_dense(ctx, x0_host, ctx->host_pad);
+    e = hipMemcpyAsync(ctx->at<float>(ctx->cv.mean), ctx->host_pad, sizeof(float) * (size_t)lo.m_pad,
                        hipMemcpyHostToDevice, ctx->stream);
   }
   if (e == hipSuccess)
@@ -581,11 +633,60 @@ int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* featur
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) {
     hip_fail(nullptr, e, "prsgd_init");
-    delete ctx;
+    release_ctx(ctx);
     return PRSGD_EHIP;
   }
   *out_ctx = ctx;
   return PRSGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int prsgd_init(const prsgd_config* cfg, const float* x0_host, const void* features_dev,
+               const void* targets_dev, void* params_dev, void* workspace_dev, void* hip_stream,
+               prsgd_ctx** out_ctx) {
+  if (out_ctx == nullptr) return set_err(nullptr, PRSGD_EINVAL, "out_ctx is null");
+  *out_ctx = nullptr;
+  return init_common(cfg, x0_host, features_dev, targets_dev, params_dev, workspace_dev, hip_stream, -1,
+                     out_ctx);
+}
+
+int prsgd_init_static(const prsgd_config* cfg, const float* x0_host, const void* features_dev,
+                      const void* targets_dev, void* params_dev, void* hip_stream, prsgd_ctx** out_ctx) {
+  if (out_ctx == nullptr) return set_err(nullptr, PRSGD_EINVAL, "out_ctx is null");
+  *out_ctx = nullptr;
+  Layout lo;
+  char err[128];
+  if (!build_layout(cfg, &lo, err, sizeof(err))) return set_err(nullptr, PRSGD_EINVAL, "%s", err);
+  Carve cv;
+  build_carve(cfg, lo, &cv);
+  if (cv.total > kStaticBytes) {
+    char msg[200];
+    snprintf(msg, sizeof(msg), "prsgd_init_static: this configuration needs %zu bytes of workspace, the "
+             "static workspace holds %zu; use prsgd_init", cv.total, kStaticBytes);
+    return set_err(nullptr, PRSGD_EINVAL, "%s", msg);
+  }
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxStaticDevices)
+    return set_err(nullptr, PRSGD_EINVAL, "prsgd_init_static: device index beyond the static slots");
+  void* ws = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticSlot& slot = g_static[dev];
+    if (slot.ws_dev == nullptr) {                  // once per device, with that device current
+      void* ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || ptr == nullptr)
+        return hip_fail(nullptr, e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress");
+      slot.ws_dev = ptr;
+    }
+    ws = slot.ws_dev;
+  }
+  return init_common(cfg, x0_host, features_dev, targets_dev, params_dev, ws, hip_stream, dev, out_ctx);
 }
 
 int prsgd_local_steps(prsgd_ctx* ctx, int32_t k) {
@@ -740,11 +841,11 @@ int prsgd_read_params(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t m)
   } else {
     src = ctx->params + (size_t)worker * ctx->lo.m_pad;
   }
-  hipError_t e = hipMemcpyAsync(ctx->host_pad.data(), src, sizeof(float) * (size_t)ctx->lo.m_pad,
+  hipError_t e = hipMemcpyAsync(ctx->host_pad, src, sizeof(float) * (size_t)ctx->lo.m_pad,
                                 hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_params");
-  dense_from_pad(ctx, ctx->host_pad.data(), out_host);
+  dense_from_pad(ctx, ctx->host_pad, out_host);
   return PRSGD_OK;
 }
 
@@ -760,24 +861,24 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
   if (ctx->poisoned) {                      // an aborted epoch launch: usable again once every
     if (worker < 0) {                       // replica has been rewritten
       ctx->poisoned = false;
-    } else if (!ctx->restored[(size_t)worker]) {
-      ctx->restored[(size_t)worker] = 1;
+    } else if (!((ctx->restored[worker >> 3] >> (worker & 7)) & 1)) {
+      ctx->restored[worker >> 3] |= (unsigned char)(1u << (worker & 7));
       if (++ctx->n_restored == (size_t)ctx->cfg.n_workers) ctx->poisoned = false;
     }
   }
   ctx->at_mean = false;
-  pad_from_dense(ctx, in_host, ctx->host_pad.data());
+  pad_from_dense(ctx, in_host, ctx->host_pad);
   const size_t bytes = sizeof(float) * (size_t)ctx->lo.m_pad;
   hipError_t e;
   if (worker < 0) {
-    e = hipMemcpyAsync(ctx->at<float>(ctx->cv.mean), ctx->host_pad.data(), bytes, hipMemcpyHostToDevice,
+    e = hipMemcpyAsync(ctx->at<float>(ctx->cv.mean), ctx->host_pad, bytes, hipMemcpyHostToDevice,
                        ctx->stream);
     if (e == hipSuccess)
       e = launch_broadcast(ctx->at<float>(ctx->cv.mean), ctx->params, ctx->shadow(), ctx->lo.m_pad,
                            ctx->cfg.n_workers, ctx->stream);
   } else {
     float* dst = ctx->params + (size_t)worker * ctx->lo.m_pad;
-    e = hipMemcpyAsync(dst, ctx->host_pad.data(), bytes, hipMemcpyHostToDevice, ctx->stream);
+    e = hipMemcpyAsync(dst, ctx->host_pad, bytes, hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess && ctx->bf16)
       e = launch_refresh_shadow(dst, ctx->shadow() + (size_t)worker * ctx->lo.m_pad, ctx->lo.m_pad,
                                 ctx->stream);
@@ -795,11 +896,11 @@ int prsgd_read_velocity(prsgd_ctx* ctx, int32_t worker, float* out_host, size_t 
   if (ctx->velocity() == nullptr) return set_err(ctx, PRSGD_ESTATE, "the context has no momentum buffers");
   const int arc = check_fused2_abort(ctx);
   if (arc != PRSGD_OK) return arc;
-  hipError_t e = hipMemcpyAsync(ctx->host_pad.data(), ctx->velocity() + (size_t)worker * ctx->lo.m_pad,
+  hipError_t e = hipMemcpyAsync(ctx->host_pad, ctx->velocity() + (size_t)worker * ctx->lo.m_pad,
                                 sizeof(float) * (size_t)ctx->lo.m_pad, hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_velocity");
-  dense_from_pad(ctx, ctx->host_pad.data(), out_host);
+  dense_from_pad(ctx, ctx->host_pad, out_host);
   return PRSGD_OK;
 }
 
@@ -809,8 +910,8 @@ int prsgd_write_velocity(prsgd_ctx* ctx, int32_t worker, const float* in_host, s
   if (m != (size_t)ctx->lo.m) return set_err(ctx, PRSGD_EINVAL, "m does not match the parameter count");
   if (worker < 0 || worker >= ctx->cfg.n_workers) return set_err(ctx, PRSGD_EINVAL, "worker out of range");
   if (ctx->velocity() == nullptr) return set_err(ctx, PRSGD_ESTATE, "the context has no momentum buffers");
-  pad_from_dense(ctx, in_host, ctx->host_pad.data());
-  hipError_t e = hipMemcpyAsync(ctx->velocity() + (size_t)worker * ctx->lo.m_pad, ctx->host_pad.data(),
+  pad_from_dense(ctx, in_host, ctx->host_pad);
+  hipError_t e = hipMemcpyAsync(ctx->velocity() + (size_t)worker * ctx->lo.m_pad, ctx->host_pad,
                                 sizeof(float) * (size_t)ctx->lo.m_pad, hipMemcpyHostToDevice, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_write_velocity");
@@ -981,7 +1082,7 @@ int prsgd_destroy(prsgd_ctx* ctx) {
     (void)hipEventDestroy(ep.a);
     (void)hipEventDestroy(ep.b);
   }
-  delete ctx;
+  release_ctx(ctx);
   return e == hipSuccess ? PRSGD_OK : PRSGD_EHIP;
 }
 

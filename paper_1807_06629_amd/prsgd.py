@@ -67,6 +67,7 @@ def _load() -> ctypes.CDLL:
         "prsgd_param_stride": (sz, [cfgp]),
         "prsgd_workspace_bytes": (sz, [cfgp]),
         "prsgd_init": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]),
+        "prsgd_init_static": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]),
         "prsgd_local_steps": (ctypes.c_int, [vp, i32]),
         "prsgd_local_steps_hetero": (ctypes.c_int, [vp, vp]),
         "prsgd_average": (ctypes.c_int, [vp]),
@@ -135,7 +136,7 @@ class Handle:
     m: int
     stride: int
     params: torch.Tensor
-    workspace: torch.Tensor
+    workspace: Optional[torch.Tensor]
     features: torch.Tensor
     targets: torch.Tensor
     stream: torch.cuda.Stream
@@ -163,8 +164,8 @@ def prsgd_workspace_bytes(cfg: prsgd_config) -> int:
     return int(_lib.prsgd_workspace_bytes(ctypes.byref(cfg)))
 
 
-def prsgd_init(cfg: prsgd_config, x0: np.ndarray, features: torch.Tensor, targets: torch.Tensor,
-               stream: Optional[torch.cuda.Stream] = None) -> Handle:
+def _init(cfg: prsgd_config, x0: np.ndarray, features: torch.Tensor, targets: torch.Tensor,
+          stream: Optional[torch.cuda.Stream], static: bool) -> Handle:
     m = prsgd_param_count(cfg)
     if m == 0:
         _lib.prsgd_init(ctypes.byref(cfg), None, None, None, None, None, None,
@@ -189,14 +190,31 @@ def prsgd_init(cfg: prsgd_config, x0: np.ndarray, features: torch.Tensor, target
         stream = torch.cuda.current_stream(dev)
     stride = prsgd_param_stride(cfg)
     params = torch.empty(n * stride, dtype=torch.float32, device=dev)
-    workspace = torch.empty(max(prsgd_workspace_bytes(cfg), 256), dtype=torch.uint8, device=dev)
     ctx = ctypes.c_void_p()
     with torch.cuda.device(dev):
-        rc = _lib.prsgd_init(ctypes.byref(cfg), x0.ctypes.data, features.data_ptr(), targets.data_ptr(),
-                             params.data_ptr(), workspace.data_ptr(), _stream_ptr(stream),
-                             ctypes.byref(ctx))
+        if static:
+            workspace = None
+            rc = _lib.prsgd_init_static(ctypes.byref(cfg), x0.ctypes.data, features.data_ptr(),
+                                        targets.data_ptr(), params.data_ptr(), _stream_ptr(stream),
+                                        ctypes.byref(ctx))
+        else:
+            workspace = torch.empty(max(prsgd_workspace_bytes(cfg), 256), dtype=torch.uint8, device=dev)
+            rc = _lib.prsgd_init(ctypes.byref(cfg), x0.ctypes.data, features.data_ptr(), targets.data_ptr(),
+                                 params.data_ptr(), workspace.data_ptr(), _stream_ptr(stream),
+                                 ctypes.byref(ctx))
     _check(rc, None)
     return Handle(ctx, cfg, m, stride, params, workspace, features, targets, stream)
+
+
+def prsgd_init(cfg: prsgd_config, x0: np.ndarray, features: torch.Tensor, targets: torch.Tensor,
+               stream: Optional[torch.cuda.Stream] = None) -> Handle:
+    return _init(cfg, x0, features, targets, stream, static=False)
+
+
+def prsgd_init_static(cfg: prsgd_config, x0: np.ndarray, features: torch.Tensor, targets: torch.Tensor,
+                      stream: Optional[torch.cuda.Stream] = None) -> Handle:
+    """prsgd_init on the library's static workspace (the replica buffer is still the caller's)."""
+    return _init(cfg, x0, features, targets, stream, static=True)
 
 
 def prsgd_local_steps(h: Handle, k: int) -> None:
