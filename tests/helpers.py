@@ -40,3 +40,16 @@ def small_mlp(**kw) -> Workload:
 
 def inputs_for(w: Workload):
     return make_inputs(w)
+
+
+def oracle_full_run(name: str, interval: int):
+    """A workload's whole oracle trajectory; meant to run in a spawned process (numpy only) while
+    the GPU tests go on.  The small configurations are bound by Python overhead, so one BLAS
+    thread is enough and keeps the cores free for the other oracle runs."""
+    from threadpoolctl import threadpool_limits
+    from workloads import get_workload
+    w = get_workload(name)
+    inp = make_inputs(w)
+    with threadpool_limits(limits=1):
+        out = oracle_run(w, inp, interval=interval)
+    return interval, out["x"], out["losses"]

@@ -20,6 +20,28 @@ pytestmark = pytest.mark.gpu
 ONE_STEP_TOL = 1e-5
 T_STEP_TOL = 1e-3
 BF16_LOSS_TOL = 2e-2
+# Absolute floor of every bf16 loss comparison: the loss head evaluates log(sum exp) in fp32,
+# which resolves a nearly saturated row (loss below ~1e-6) only to 2^-23..2^-24; 8 ulps of 1.
+LOSS_QUANTUM = 2.0 ** -20
+# Free-running multi-step trajectories of the c3 recipe (gamma = 0.05, unnormalised 3072-dimensional
+# inputs: the loss explodes, then collapses) amplify rounding differences chaotically: one bf16
+# unit in the last place of one input value moves the loss ~1e-2 relative within six steps
+# (tests/test_bf16_sensitivity.py, on the oracle alone).  Such runs are held to this band; the
+# 2e-2 gate is applied to every step taken from the oracle's own point.
+BF16_FREE_RUN_BAND = 1e-1
+
+
+def _bf16_loss_ok(got, want, rtol=BF16_LOSS_TOL):
+    return bool(np.all(np.abs(got - want) <= rtol * np.abs(want) + LOSS_QUANTUM))
+
+
+def _resync(P, h, rec):
+    """Puts the GPU on the oracle's point after the recorded iteration (fp32-rounded)."""
+    if rec["averaged"]:
+        P.prsgd_write_params(h, -1, rec["x_after"][0].astype(np.float32))
+    else:
+        for i in range(rec["x_after"].shape[0]):
+            P.prsgd_write_params(h, i, rec["x_after"][i].astype(np.float32))
 
 
 @pytest.fixture(scope="module")
@@ -254,19 +276,22 @@ def test_mlp_bf16_loss_and_parameters(P, D, shape, fused):
 def test_c3_shape_noniid_reduced(P, D):
     w = get_workload("c3").scaled(n_workers=4, rows_per_worker=512, iterations=6, interval=3)
     inp = make_inputs(w)
-    h = _open(D, w, inp)
+    free, sync = _open(D, w, inp), _open(D, w, inp)
     log = []
     want = oracle_run(w, inp, record=log.append)
-    # loss of every iteration; once the (nearly separable) minibatch loss has fallen below
-    # ~1e-2 a single bf16 rounding flip of one activation moves it by more than 2 %, so the
-    # relative gate carries an absolute floor of 2e-2 * 0.02
     for rec in log:
-        P.prsgd_run(h, 1, w.interval)
-        got = P.prsgd_read_loss(h)
-        assert np.allclose(got, rec["losses"], rtol=BF16_LOSS_TOL, atol=BF16_LOSS_TOL * 0.02), \
-            (rec["t"], got, rec["losses"])
-    assert rel_err(D.read_all(h), want["x"]) <= 5e-3
-    P.prsgd_destroy(h)
+        # every step from the oracle's own point: the stated gate; free-running: the band
+        P.prsgd_run(sync, 1, w.interval)
+        got = P.prsgd_read_loss(sync)
+        assert _bf16_loss_ok(got, rec["losses"]), (rec["t"], got, rec["losses"])
+        assert rel_err(D.read_all(sync), rec["x_after"]) <= 1e-3
+        _resync(P, sync, rec)
+        P.prsgd_run(free, 1, w.interval)
+        got = P.prsgd_read_loss(free)
+        assert _bf16_loss_ok(got, rec["losses"], BF16_FREE_RUN_BAND), (rec["t"], got, rec["losses"])
+    assert rel_err(D.read_all(free), want["x"]) <= 5e-3
+    P.prsgd_destroy(free)
+    P.prsgd_destroy(sync)
 
 
 def test_bf16_fused_backward_kernel_runs_and_falls_back_above_128_rows(P, D):
@@ -326,8 +351,9 @@ def test_c4_full_shape_long_run(P, D, interval):
 
 @pytest.mark.parametrize("name,iters,interval", [("c3", 4, 2), ("c5", 2, 2)])
 def test_bf16_full_size_replicas(P, D, name, iters, interval):
-    # full layer sizes, worker count and batch (the launch shapes the benchmark times); a short
-    # horizon and a smaller shard keep the fp64 oracle to seconds
+    # full layer sizes, worker count and batch (the launch shapes the benchmark times) with a
+    # restart every second step; a short horizon and a smaller shard keep the fp64 oracle to
+    # seconds (the configurations' own intervals and shards: tests/test_gpu_horizons.py)
     w = get_workload(name).scaled(rows_per_worker=512, iterations=iters, interval=interval)
     inp = make_inputs(w)
     h = _open(D, w, inp)
@@ -336,8 +362,7 @@ def test_bf16_full_size_replicas(P, D, name, iters, interval):
     for rec in log:
         P.prsgd_run(h, 1, w.interval)
         got = P.prsgd_read_loss(h)
-        assert np.allclose(got, rec["losses"], rtol=BF16_LOSS_TOL, atol=BF16_LOSS_TOL * 0.02), \
-            (rec["t"], got, rec["losses"])
+        assert _bf16_loss_ok(got, rec["losses"]), (rec["t"], got, rec["losses"])
     # sampled replicas, every parameter
     for i in (0, w.n_workers - 1):
         assert rel_err(P.prsgd_read_params(h, i), want["x"][i]) <= 5e-3
@@ -448,9 +473,8 @@ def test_deferred_broadcast_gives_the_same_run_as_the_averaging_kernel(P, D, kin
         assert np.array_equal(a, b)
     want = oracle_run(w, inp, interval=interval)
     if kind == "bf16":
-        # nine steps amplify single bf16 rounding flips of an activation: the gate is on the loss
-        assert np.allclose(outs[0][2], want["losses"], rtol=BF16_LOSS_TOL)
-        assert rel_err(outs[0][0], want["x"]) <= 2e-2
+        assert _bf16_loss_ok(outs[0][2], want["losses"])
+        assert rel_err(outs[0][0], want["x"]) <= 5e-3
     else:
         assert rel_err(outs[0][0], want["x"]) <= 1e-4
 
@@ -627,8 +651,11 @@ def test_momentum_local_steps(P, D, kind, kw, mode):
     got_x = D.read_all(h)
     got_v = np.stack([P.prsgd_read_velocity(h, i) for i in range(w.n_workers)])
     if kind.startswith("bf16"):
-        assert np.allclose(P.prsgd_read_loss(h), want["losses"], rtol=BF16_LOSS_TOL)
-        assert rel_err(got_x, want["x"]) <= 2e-2
+        assert _bf16_loss_ok(P.prsgd_read_loss(h), want["losses"])
+        assert rel_err(got_x, want["x"]) <= 5e-3
+        # right after a reset the velocity is one or two raw gradients: a hidden pre-activation
+        # that fp32 accumulation puts on the other side of zero switches one sample's share of a
+        # dW column on or off (ReLU'), up to 1/B of that column (B = 100 in the widest case)
         assert rel_err(got_v, want["v"]) <= 2e-2
     else:
         assert rel_err(got_x, want["x"]) <= 1e-4
