@@ -8,7 +8,7 @@
 //   weights   dW_l   = H_{l-1}^T D_l ; db_l = colsum(D_l)  M = d_{l-1}, N = d_l,     Kc = B
 //             fused with the local update  W_l <- W_l - gamma dW_l      (Algorithm 1, eq. 3)
 //
-// A workgroup is 4 wavefronts; each wavefront owns TM x TN accumulator tiles of 32x32
+// A workgroup is 4 wavefronts (8 on the widest tile); each wavefront owns TM x TN accumulator tiles of 32x32
 // (v_mfma_f32_32x32x16_bf16 or v_mfma_f32_32x32x2_f32).  Operand tiles are staged through LDS in
 // their natural memory orientation with 16-byte global loads; an operand whose contraction
 // index is the strided one is transposed while its MFMA fragments are read out of LDS.
@@ -36,7 +36,10 @@ struct TBF16 {
   using frag = bf16x8_t;
   static constexpr int V = 8;
   static constexpr int KSTEP = 16;
-  static constexpr int BK = 64;
+#ifndef PRSGD_BF16_BK
+#define PRSGD_BF16_BK 64
+#endif
+  static constexpr int BK = PRSGD_BF16_BK;
   static constexpr int PADC = 8;
   static constexpr int PADT = 16;    // 4 consecutive k rows of a transpose read hit distinct banks
   static constexpr bool kBf16 = true;
@@ -62,12 +65,12 @@ template <typename T, int ROWS, int KIND> struct TileShape {
 //   OP_TRANS : element (r, c) at src[c * ld + r]; LDS [BK][ROWS + PADT]
 // Vector loads run along the memory-contiguous index; a vector that starts inside the logical
 // extent may run into the zero padding every buffer carries up to a multiple of 8 elements.
-template <typename T, int ROWS, int KIND> struct TileIO {
+template <typename T, int ROWS, int KIND, int NTHR = kThreads> struct TileIO {
   using E = typename T::elem;
   static constexpr int V = T::V, BK = T::BK;
   static constexpr int VECS = ROWS * BK / V;
-  static constexpr int NPT = VECS / kThreads;            // vectors per thread
-  static_assert(VECS % kThreads == 0, "tile must split evenly over the workgroup");
+  static constexpr int NPT = VECS / NTHR;                // vectors per thread
+  static_assert(VECS % NTHR == 0, "tile must split evenly over the workgroup");
   static constexpr int STRIDE = TileShape<T, ROWS, KIND>::kStride;
 
   // Returns the validity mask of the NPT vectors (bit q set = inside the operand).
@@ -76,7 +79,7 @@ template <typename T, int ROWS, int KIND> struct TileIO {
     uint32_t mask = 0;
 #pragma unroll
     for (int q = 0; q < NPT; ++q) {
-      const int v = q * kThreads + tid;
+      const int v = q * NTHR + tid;
       // Branch-free: an out-of-range vector loads element (0, 0) instead and is zeroed when it
       // is written to LDS, so nothing waits on the load here and the loads stay countable for
       // the compiler's vmcnt bookkeeping across the pipeline.
@@ -103,7 +106,7 @@ template <typename T, int ROWS, int KIND> struct TileIO {
                                                uint32_t mask, int tid) {
 #pragma unroll
     for (int q = 0; q < NPT; ++q) {
-      const int v = q * kThreads + tid;
+      const int v = q * NTHR + tid;
       const uint32_t keep = 0u - ((mask >> q) & 1u);      // all ones inside the operand, else zero
       uint4 reg[1];
       reg[0] = make_uint4(reg_in[q].x & keep, reg_in[q].y & keep, reg_in[q].z & keep, reg_in[q].w & keep);
@@ -157,14 +160,15 @@ __device__ __forceinline__ float act_bwd_from_h(float h, int act) {
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND>
-__global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
+__global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) {
   using E = typename T::elem;
-  using IOA = TileIO<T, BM, AKIND>;
-  using IOB = TileIO<T, BN, BKIND>;
+  constexpr int NTHR = 64 * WM * WN;
+  using IOA = TileIO<T, BM, AKIND, NTHR>;
+  using IOB = TileIO<T, BN, BKIND, NTHR>;
   constexpr int BK = T::BK;
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   constexpr int A_ELEMS = TileShape<T, BM, AKIND>::kElems, B_ELEMS = TileShape<T, BN, BKIND>::kElems;
-  static_assert(WM * WN == 4, "4 wavefronts per workgroup");
+  static_assert(WM * WN == 4 || WM * WN == 8, "4 or 8 wavefronts per workgroup");
   static_assert(TM >= 1 && TN >= 1, "tile too small for the wavefront grid");
   static_assert((A_ELEMS * sizeof(E)) % 16 == 0 && (B_ELEMS * sizeof(E)) % 16 == 0, "LDS alignment");
 
@@ -265,12 +269,13 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   IOA::stash(a_lds0, a_r[0], a_m[0], tid);
   IOB::stash(b_lds0, b_r[0], b_m[0], tid);
   if constexpr (kDeep) {
+    // Unconditional: a tile past the end of the contraction is fetched masked (all vectors read
+    // element (0, 0) and are zeroed on the way to LDS).  Straight-line code keeps the number of
+    // loads in flight the same on every path, which the wait-count bookkeeping needs.
 #pragma unroll
     for (int j = 1; j <= R; ++j) {
-      if (j < n_k) {
-        a_m[j % R] = IOA::fetch(a_r[j % R], a_src, p.lda, m0, p.M, j * BK, Kc, tid);
-        b_m[j % R] = IOB::fetch(b_r[j % R], b_src, p.ldb, n0, p.N, j * BK, Kc, tid);
-      }
+      a_m[j % R] = IOA::fetch(a_r[j % R], a_src, p.lda, m0, p.M, j * BK, Kc, tid);
+      b_m[j % R] = IOB::fetch(b_r[j % R], b_src, p.ldb, n0, p.N, j * BK, Kc, tid);
     }
   }
   __syncthreads();
@@ -307,37 +312,29 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_kernel(GemmArgs p) {
   if constexpr (kDeep) {
     // One pipeline step on tile `it` (it % R == U): multiply the LDS stage it & 1, move tile
     // it+1 from its register set to the other stage, refill that set with tile it+1+R.
-    // STEADY = all of these tiles exist: straight-line code, so the loads of the other register
-    // sets can stay in flight across the step.
-    auto step = [&](int it, auto u_tag, auto steady_tag) {
+    // Straight-line code without a single conditional load: the hardware counts outstanding
+    // memory operations in issue order, and the compiler can only leave the loads of the other
+    // register sets in flight across a step if their number is the same on every path (a
+    // conditional prologue or drain loop made it wait for ALL of them once per R steps).
+    auto step = [&](int it, auto u_tag) {
       constexpr int U = decltype(u_tag)::value;
-      constexpr bool STEADY = decltype(steady_tag)::value;
       constexpr int SET = (U + 1) % R, CUR = U & 1;
       compute(CUR);
-      if (STEADY || it + 1 < n_k) {
-        IOA::stash(a_lds0 + (CUR ^ 1) * A_ELEMS, a_r[SET], a_m[SET], tid);
-        IOB::stash(b_lds0 + (CUR ^ 1) * B_ELEMS, b_r[SET], b_m[SET], tid);
-      }
-      if (STEADY || it + 1 + R < n_k) {
-        a_m[SET] = IOA::fetch(a_r[SET], a_src, p.lda, m0, p.M, (it + 1 + R) * BK, Kc, tid);
-        b_m[SET] = IOB::fetch(b_r[SET], b_src, p.ldb, n0, p.N, (it + 1 + R) * BK, Kc, tid);
-      }
+      IOA::stash(a_lds0 + (CUR ^ 1) * A_ELEMS, a_r[SET], a_m[SET], tid);
+      IOB::stash(b_lds0 + (CUR ^ 1) * B_ELEMS, b_r[SET], b_m[SET], tid);
+      a_m[SET] = IOA::fetch(a_r[SET], a_src, p.lda, m0, p.M, (it + 1 + R) * BK, Kc, tid);
+      b_m[SET] = IOB::fetch(b_r[SET], b_src, p.ldb, n0, p.N, (it + 1 + R) * BK, Kc, tid);
       __syncthreads();
     };
     static_assert(R == 4, "the unrolled pipeline below is written for four register sets");
     using std::integral_constant;
-    int it = 0;
-    for (; it + 2 * R < n_k; it += R) {        // tiles up to it+3+1+R exist: no conditionals inside
-      step(it, integral_constant<int, 0>{}, integral_constant<bool, true>{});
-      step(it + 1, integral_constant<int, 1>{}, integral_constant<bool, true>{});
-      step(it + 2, integral_constant<int, 2>{}, integral_constant<bool, true>{});
-      step(it + 3, integral_constant<int, 3>{}, integral_constant<bool, true>{});
-    }
-    for (; it < n_k; it += R) {                // drain (it stays a multiple of R)
-      step(it, integral_constant<int, 0>{}, integral_constant<bool, false>{});
-      if (it + 1 < n_k) step(it + 1, integral_constant<int, 1>{}, integral_constant<bool, false>{});
-      if (it + 2 < n_k) step(it + 2, integral_constant<int, 2>{}, integral_constant<bool, false>{});
-      if (it + 3 < n_k) step(it + 3, integral_constant<int, 3>{}, integral_constant<bool, false>{});
+    // Every group of R steps runs the straight-line form: tiles past the end arrive as zeros
+    // (masked fetch) and add nothing, at the cost of at most R - 1 empty steps per workgroup.
+    for (int it = 0; it < n_k; it += R) {
+      step(it, integral_constant<int, 0>{});
+      step(it + 1, integral_constant<int, 1>{});
+      step(it + 2, integral_constant<int, 2>{});
+      step(it + 3, integral_constant<int, 3>{});
     }
   } else {
     for (int it = 0; it < n_k; ++it) {         // single LDS stage, next tile prefetched in registers
@@ -455,7 +452,7 @@ static hipError_t launch_one(GemmArgs p, int n_groups, hipStream_t s) {
   p.n_groups = n_groups;
   if (p.k_splits > 1 && p.epi != EPI_FWD_LOGITS) return hipErrorInvalidValue;
   const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN) * (p.k_splits > 1 ? p.k_splits : 1);
-  hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles * n_groups)), dim3(kThreads), kLds, s, p);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles * n_groups)), dim3(64 * WM * WN), kLds, s, p);
   return hipGetLastError();
 }
 
@@ -473,7 +470,9 @@ static hipError_t launch_rows(const GemmArgs& p, int n_groups, hipStream_t s) {
     if (wide) return launch_one<T, 64, 128, 2, 2, AKIND, BKIND>(p, n_groups, s);
     return launch_one<T, 64, 64, 2, 2, AKIND, BKIND>(p, n_groups, s);
   }
-  if (wide) return launch_one<T, 128, 128, 2, 2, AKIND, BKIND>(p, n_groups, s);
+  // eight wavefronts on the widest tile: with one wavefront per SIMD nothing covers the LDS
+  // latency between fragment reads and matrix instructions (4096 x 4096, 8 replicas: 74 -> 61 us)
+  if (wide) return launch_one<T, 128, 128, 2, 4, AKIND, BKIND>(p, n_groups, s);
   // a narrow layer that would leave compute units idle splits the minibatch rows over two
   // workgroups instead: the second reader of a weight tile finds it in the L2 of the same XCD
   if ((long)((p.N + 63) / 64) * n_groups < kComputeUnits)
