@@ -31,7 +31,8 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 KERNEL_SYMBOL = {
     "gather": "gather_kernel", "gemm_fwd": "grouped_gemm_kernel<.., OP_CONTIG, OP_TRANS>",
     "gemm_dx": "grouped_gemm_kernel<.., OP_CONTIG, OP_CONTIG>",
-    "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>", "gemm_bwd": "grouped_bwd_kernel",
+    "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>",
+    "gemm_bwd": "grouped_bwd_full_kernel (grouped_bwd_kernel for layers with partial tiles)",
     "softmax_xent": "softmax_xent_kernel",
     "sgd_update": "update_kernel",
     "average": "average_kernel (restart_small_kernel<.., true> when N >= 8 and a replica has fewer "
@@ -40,13 +41,18 @@ KERNEL_SYMBOL = {
                     "fewer than 262144 floats)",
     "lsq_steps": "lsq_steps_staged_kernel (lsq_steps_kernel for shapes it does not take)",
     "mlp2_epoch": "mlp2_epoch_kernel",
+    "step_mean": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS, true> (the minibatches of all workers "
+                 "stacked into one contraction)",
 }
 
 
-def algorithmic_work(w):
+def algorithmic_work(w, shared_weights=False):
     """Algorithmic HBM bytes and flops of ONE iteration, per kernel label (all launches of
-    that label in the iteration summed), plus those of one restart average."""
+    that label in the iteration summed), plus those of one restart average.  shared_weights:
+    every iteration starts from the node average (I = 1, one-pass form), so the forward and
+    backward-data products read one weight matrix per layer instead of one per worker."""
     n, b = w.n_workers, w.batch
+    nw = 1 if shared_weights else n
     out = {}
     if w.model == "lsq":
         d = w.dims[0]
@@ -60,9 +66,9 @@ def algorithmic_work(w):
     m = sum(di * do + do for di, do in layers)
     pw = sum(di * do for di, do in layers)
     shadow = 2 if w.gemm_dtype == "bf16" else 0
-    fwd_b = sum(n * (di * do * es + b * di * es + b * do * es) for di, do in layers)
+    fwd_b = sum(nw * di * do * es + n * (b * di * es + b * do * es) for di, do in layers)
     fwd_f = sum(2 * n * b * di * do for di, do in layers)
-    dx_b = sum(n * (di * do * es + b * do * es + 2 * b * di * es) for di, do in layers[1:])
+    dx_b = sum(nw * di * do * es + n * (b * do * es + 2 * b * di * es) for di, do in layers[1:])
     dx_f = sum(2 * n * b * di * do for di, do in layers[1:])
     dw_b = sum(n * (di * do * (8 + shadow) + b * (di + do) * es) for di, do in layers)
     dw_f = fwd_f
@@ -86,6 +92,10 @@ def algorithmic_work(w):
     # restart with the broadcast deferred: every replica read once, the node average (and its
     # bf16 image) written once
     out["restart_mean"] = {"bytes": n * m * 4 + m * 4 + pw * shadow, "flops": n * m}
+    # I = 1, step and restart in one pass: the node average read and written once (+ bf16 image),
+    # every worker's activation and delta panels read once; the weight-gradient product
+    out["step_mean"] = {"bytes": m * 8 + pw * shadow + sum(n * b * (di + do) * 2 for di, do in layers),
+                        "flops": dw_f}
     return out
 
 
@@ -324,7 +334,9 @@ def main() -> int:
     stats = prsgd.prsgd_profile_read(h)
     prsgd.prsgd_profile_enable(h, False)
 
-    work = algorithmic_work(w)
+    one_pass = (w.interval == 1 and w.model == "mlp" and w.gemm_dtype == "bf16" and not args.unfused
+                and not args.eager_restart and w.momentum == 0.0 and w.batch <= 128)
+    work = algorithmic_work(w, shared_weights=one_pass)
     kernels = {}
     for s in stats:
         per_iter = work.get(s["name"], {"bytes": 0, "flops": 0})

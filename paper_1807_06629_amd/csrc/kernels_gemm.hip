@@ -159,7 +159,10 @@ __device__ __forceinline__ float act_bwd_from_h(float h, int act) {
   return act == PRSGD_TANH ? (1.0f - h * h) : (h > 0.0f ? 1.0f : 0.0f);
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND>
+// DEEP: the two-stage, four-register-set pipeline (long contractions); otherwise a single LDS
+// stage with a one-tile prefetch (the per-replica weight-gradient product: one or two tiles).
+template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND,
+          bool DEEP = !(AKIND == OP_TRANS && BKIND == OP_TRANS)>
 __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) {
   using E = typename T::elem;
   constexpr int NTHR = 64 * WM * WN;
@@ -193,9 +196,9 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // Two LDS stages of each operand tile; the weight-gradient product (one or two contraction
-  // tiles in all) keeps a single stage so that more workgroups fit on a compute unit.
-  constexpr int kStages = (AKIND == OP_TRANS && BKIND == OP_TRANS) ? 1 : 2;
+  // Two LDS stages of each operand tile; the per-replica weight-gradient product (one or two
+  // contraction tiles in all) keeps a single stage so that more workgroups fit on a compute unit.
+  constexpr int kStages = DEEP ? 2 : 1;
   E* const a_lds0 = reinterpret_cast<E*>(smem);
   E* const b_lds0 = a_lds0 + kStages * A_ELEMS;
 
@@ -254,10 +257,10 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
   // Software pipeline: two LDS stages and R register sets, so that the global loads of tiles
   // it+2 .. it+1+R are all in flight while tile `it` is multiplied -- one tile of compute is far
   // shorter than the HBM latency it has to hide, and a launch has few workgroups per compute unit.
-  // Tile j (j >= 1) travels through register set j % R.  The weight-gradient product contracts
-  // over the minibatch only (one or two tiles): it keeps a single LDS stage and a one-tile
-  // prefetch and spends its registers on the streamed weights instead.
-  constexpr bool kDeep = !kIsDw;
+  // Tile j (j >= 1) travels through register set j % R.  The per-replica weight-gradient product
+  // contracts over the minibatch only (one or two tiles): it keeps a single LDS stage and a
+  // one-tile prefetch and spends its registers on the streamed weights instead.
+  constexpr bool kDeep = DEEP;
   constexpr int R = kDeep ? 4 : 1;
   const int n_k = (Kc + BK - 1) / BK;
   uint4 a_r[R][IOA::NPT], b_r[R][IOB::NPT];
@@ -433,14 +436,15 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
     }
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND>
+template <typename T, int BM, int BN, int WM, int WN, int AKIND, int BKIND,
+          bool DEEP = !(AKIND == OP_TRANS && BKIND == OP_TRANS)>
 static hipError_t launch_one(GemmArgs p, int n_groups, hipStream_t s) {
   if (p.M <= 0 || p.N <= 0 || n_groups <= 0) return hipSuccess;
   using E = typename T::elem;
-  constexpr size_t kStages = (AKIND == OP_TRANS && BKIND == OP_TRANS) ? 1 : 2;
+  constexpr size_t kStages = DEEP ? 2 : 1;
   constexpr size_t kLds =
       kStages * sizeof(E) * (TileShape<T, BM, AKIND>::kElems + TileShape<T, BN, BKIND>::kElems);
-  auto kernel = grouped_gemm_kernel<T, BM, BN, WM, WN, AKIND, BKIND>;
+  auto kernel = grouped_gemm_kernel<T, BM, BN, WM, WN, AKIND, BKIND, DEEP>;
   // double-buffered tiles can exceed the 64 KB default; setting the limit twice is harmless
   static std::atomic<bool> configured{false};
   if (!configured.load(std::memory_order_acquire)) {
@@ -517,6 +521,15 @@ hipError_t launch_gemm_dx(const GemmArgs& p, int n_groups, bool bf16, hipStream_
 hipError_t launch_gemm_dw(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s) {
   return bf16 ? launch_one<TBF16, 128, 64, 2, 2, OP_TRANS, OP_TRANS>(p, n_groups, s)
               : launch_one<TF32, 128, 64, 2, 2, OP_TRANS, OP_TRANS>(p, n_groups, s);
+}
+// The same product with the minibatches of all workers stacked into one contraction (a single
+// group, Kc = N B rows): a long contraction, so the deep pipeline and the widest tile that still
+// fills the chip.
+hipError_t launch_gemm_dw_stacked(const GemmArgs& p, hipStream_t s) {
+  const long wide_tiles = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+  if (wide_tiles >= kComputeUnits)
+    return launch_one<TBF16, 128, 128, 2, 4, OP_TRANS, OP_TRANS, true>(p, 1, s);
+  return launch_one<TBF16, 128, 64, 2, 2, OP_TRANS, OP_TRANS, true>(p, 1, s);
 }
 
 }  // namespace prsgd

@@ -19,7 +19,7 @@ namespace prsgd {
 const char* kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
                                         "sgd_update", "average", "mean",       "broadcast", "lsq_steps",
-                                        "mlp2_epoch", "gemm_bwd", "restart_mean"};
+                                        "mlp2_epoch", "gemm_bwd", "restart_mean", "step_mean"};
   return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
 }
 }  // namespace prsgd
@@ -258,7 +258,12 @@ struct Timed {
 int materialize(prsgd_ctx* ctx);
 
 // One local iteration of every (active) MLP worker: gradient observation + eq. (3).
-int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
+// fuse_average (interval I = 1, every worker at the node average ybar): step and restart together
+// are one mini-batch SGD step on ybar with the N B samples of all workers (first footnote of
+// Section 1): (1/N) sum_i (ybar - gamma G_i) = ybar - (gamma / N) sum_i G_i.  The backward pass
+// contracts over the stacked minibatches and writes only the new ybar; the replicas stay stale
+// and the context stays "at the mean".
+int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool fuse_average = false) {
   const prsgd_config& c = ctx->cfg;
   const Layout& lo = ctx->lo;
   const Carve& cv = ctx->cv;
@@ -330,6 +335,36 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step) {
                              ctx->at<int32_t>(cv.yb),
                              ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.row_loss), N, B, lo.d[L],
                              lo.ld[L], bf16, worker_steps, step, s));
+
+  if (fuse_average) {
+    // eq. (3) from the common point and eq. (2) in one pass over ybar, layer by layer from the
+    // top: D_{l-1} needs the old ybar_l (its bf16 image), so it runs before layer l's pass
+    for (int l = L; l >= 1; --l) {
+      if (l > 1) {
+        GemmArgs p = base;
+        p.a = ctx->at<void>(cv.delta[l]); p.a_gs = (long)B * lo.ld[l]; p.lda = lo.ld[l];
+        p.b = (const void*)(ctx->mean_shadow() + lo.w_off[l - 1]); p.b_gs = 0; p.ldb = lo.ld[l];
+        p.M = B; p.N = lo.d[l - 1]; p.Kc = lo.d[l];
+        p.epi = EPI_DX;
+        p.out = ctx->at<void>(cv.delta[l - 1]); p.out_gs = (long)B * lo.ld[l - 1];
+        p.ldo = lo.ld[l - 1]; p.out_cols = lo.ld[l - 1];
+        p.aux = act_in(l - 1); p.aux_gs = (long)B * lo.ld[l - 1]; p.ldaux = lo.ld[l - 1];
+        LAUNCH(ctx, KK_DX, launch_gemm_dx(p, N, true, s));
+      }
+      // all minibatches stacked: sum_i dW_i = [H_1; ..; H_N]^T [D_1; ..; D_N], one contraction of N B
+      // rows, and ybar <- ybar - (gamma / N) sum_i dW_i (likewise the bias from the column sums)
+      GemmArgs p = base;
+      p.a = act_in(l - 1); p.a_gs = 0; p.lda = lo.ld[l - 1];
+      p.b = ctx->at<void>(cv.delta[l]); p.b_gs = 0; p.ldb = lo.ld[l];
+      p.M = lo.d[l - 1]; p.N = lo.d[l]; p.Kc = N * B;
+      p.epi = EPI_DW_FUSED;
+      p.lr = ctx->lr / (float)N;
+      p.params = ctx->mean(); p.shadow = ctx->mean_shadow(); p.p_gs = 0;
+      p.w_off = lo.w_off[l - 1]; p.b_off = lo.b_off[l - 1]; p.ldw = lo.ld[l];
+      LAUNCH(ctx, KK_STEP_MEAN, launch_gemm_dw_stacked(p, s));
+    }
+    return PRSGD_OK;                 // still at the (new) mean; the replicas were not touched
+  }
 
   // backward.  bf16 operands with the fused update: one kernel per layer does the weight
   // gradient, eq. (3) and the delta of the layer below in a single pass over W_l.
@@ -810,7 +845,20 @@ int prsgd_run(prsgd_ctx* ctx, int64_t iterations, int32_t interval) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (iterations < 0 || interval < 1) return set_err(ctx, PRSGD_EINVAL, "iterations >= 0, interval >= 1");
   int64_t left = iterations;
+  // I = 1 with plain SGD on bf16 operands: once the workers sit at the node average (after the
+  // first restart) every further iteration is one pass over ybar -- step and restart together
+  const bool can_fuse = interval == 1 && ctx->cfg.model == PRSGD_MLP && ctx->bf16 && ctx->cfg.fused_update &&
+                        ctx->cfg.momentum == 0.0f && ctx->lazy_restart && !ctx->use_fused2 &&
+                        bwd_fused_supported(ctx->cfg.batch);
   while (left > 0) {
+    if (can_fuse && ctx->at_mean) {
+      if (check_poisoned(ctx) != PRSGD_OK) return PRSGD_ESTATE;
+      const int rc = mlp_step(ctx, ctx->t + 1, nullptr, 0, true);
+      if (rc != PRSGD_OK) return rc;
+      ctx->t += 1;
+      left -= 1;
+      continue;
+    }
     int64_t k = interval - (ctx->t % interval);      // steps until the next multiple of I
     if (k > left) k = left;
     int rc = prsgd_local_steps(ctx, (int32_t)k);

@@ -69,7 +69,7 @@ constexpr int kMaxLogitSplits = 4;
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
-  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_COUNT
+  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_STEP_MEAN, KK_COUNT
 };
 
 // Fused backward step of one layer with bf16 operands (kernels_bwd.hip): weight gradient, local
@@ -122,6 +122,7 @@ const char* kernel_kind_name(int kind);
 // ---- launchers (each returns the hipError_t of the launch) --------------------------------
 hipError_t launch_gemm_fwd(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
 hipError_t launch_gemm_dx(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
+hipError_t launch_gemm_dw_stacked(const GemmArgs& p, hipStream_t s);   // bf16 operands, one group
 hipError_t launch_gemm_dw(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
 
 hipError_t launch_gather(const float* features, const int32_t* labels, void* xb, int32_t* yb,

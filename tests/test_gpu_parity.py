@@ -469,8 +469,17 @@ def test_deferred_broadcast_gives_the_same_run_as_the_averaging_kernel(P, D, kin
         xs, xbar = D.read_all(h), P.prsgd_read_params(h, -1)
         outs.append((xs, xbar, P.prsgd_read_loss(h)))
         P.prsgd_destroy(h)
-    for a, b in zip(outs[0], outs[1]):
-        assert np.array_equal(a, b)
+    if kind == "bf16" and interval == 1:
+        # I = 1 with the broadcast deferred takes step and restart as one mini-batch SGD step on the
+        # node average (one rounding instead of N + 1, another contraction order).  The masters differ
+        # by fp32 rounding after one iteration (tests/test_gpu_interval_one.py holds that to 1e-5);
+        # their bf16 images then differ by whole bf16 units here and there, so nine iterations later
+        # the two runs are as far apart as each is from the oracle: the bf16 gates
+        assert rel_err(outs[0][0], outs[1][0]) <= 5e-3 and rel_err(outs[0][1][None], outs[1][1][None]) <= 5e-3
+        assert _bf16_loss_ok(outs[0][2], outs[1][2])
+    else:
+        for a, b in zip(outs[0], outs[1]):
+            assert np.array_equal(a, b)
     want = oracle_run(w, inp, interval=interval)
     if kind == "bf16":
         assert _bf16_loss_ok(outs[0][2], want["losses"])
