@@ -152,6 +152,15 @@ __device__ __forceinline__ f32x16_t mfma(bf16x8_t a, bf16x8_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// A-operand fragment of all ones: with it one matrix instruction yields the column sums of the
+// B fragment (every row of the 32 x 32 result holds them).
+template <typename F> __device__ __forceinline__ F ones_frag();
+template <> __device__ __forceinline__ float ones_frag<float>() { return 1.0f; }
+template <> __device__ __forceinline__ bf16x8_t ones_frag<bf16x8_t>() {
+  const u16x8_t u = {0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80};
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+
 __device__ __forceinline__ float act_fwd(float z, int act) {
   return act == PRSGD_TANH ? tanhf(z) : fmaxf(z, 0.0f);
 }
@@ -251,8 +260,14 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const bool bias_wg = kIsDw && m0 == 0;
-  float colsum = 0.0f;                       // db: thread n sums column n of the delta tile
+  // db_l = colsum(D_l): the workgroups of the first row band feed the delta fragments they hold
+  // anyway through one more matrix instruction against an all-ones operand
+  const bool bias_wave = kIsDw && m0 == 0 && wm == 0;
+  f32x16_t accb[kIsDw ? TN : 1];
+#pragma unroll
+  for (int j = 0; j < (kIsDw ? TN : 1); ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accb[j][v] = 0.0f;
 
   // Software pipeline: two LDS stages and R register sets, so that the global loads of tiles
   // it+2 .. it+1+R are all in flight while tile `it` is multiplied -- one tile of compute is far
@@ -286,30 +301,38 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
   auto compute = [&](int cur) {
     const E* a_cur = a_lds0 + cur * A_ELEMS;
     const E* b_cur = b_lds0 + cur * B_ELEMS;
-#pragma unroll
-    for (int kk = 0; kk < BK / T::KSTEP; ++kk) {
-      typename T::frag af[TM], bf[TN];
+    constexpr int KK = BK / T::KSTEP;
+    // fragments of contraction step kk + 1 are read from LDS while the matrix instructions of
+    // step kk run: two register sets, filled alternately
+    typename T::frag af[2][TM], bf[2][TN];
+    auto load_frags = [&](int kk, int set) __attribute__((always_inline)) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int rb_ = (wm * TM + i) * 32;
-        if constexpr (T::kBf16) af[i] = load_frag_bf16<BM, AKIND>(a_cur, rb_, kk, lane);
-        else af[i] = load_frag_f32<BM, AKIND>(a_cur, rb_ + lr32, kk, kb);
+        if constexpr (T::kBf16) af[set][i] = load_frag_bf16<BM, AKIND>(a_cur, rb_, kk, lane);
+        else af[set][i] = load_frag_f32<BM, AKIND>(a_cur, rb_ + lr32, kk, kb);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int rb_ = (wn * TN + j) * 32;
-        if constexpr (T::kBf16) bf[j] = load_frag_bf16<BN, BKIND>(b_cur, rb_, kk, lane);
-        else bf[j] = load_frag_f32<BN, BKIND>(b_cur, rb_ + lr32, kk, kb);
+        if constexpr (T::kBf16) bf[set][j] = load_frag_bf16<BN, BKIND>(b_cur, rb_, kk, lane);
+        else bf[set][j] = load_frag_f32<BN, BKIND>(b_cur, rb_ + lr32, kk, kb);
       }
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + 1 < KK) load_frags(kk + 1, (kk + 1) & 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(af[i], bf[j], acc[i][j]);
-    }
-    if (kIsDw && bias_wg && tid < BN) {
-      // delta tile sits in LDS as [c][n]; rows beyond Kc were zero-filled
-#pragma unroll 8
-      for (int c = 0; c < BK; ++c) colsum += from_elem<T>(b_cur[c * IOB::STRIDE + tid]);
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(af[kk & 1][i], bf[kk & 1][j], acc[i][j]);
+      if constexpr (kIsDw) {
+        if (bias_wave) {               // rows beyond Kc were zero-filled in LDS
+#pragma unroll
+          for (int j = 0; j < TN; ++j) accb[j] = mfma(ones_frag<typename T::frag>(), bf[kk & 1][j], accb[j]);
+        }
+      }
     }
   };
   if constexpr (kDeep) {
@@ -384,14 +407,18 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
             }
           }
         }
-    if (bias_wg && tid < BN) {
-      const int n = n0 + tid;
-      if (n < p.N) {
-        if (fused) {
-          float* bptr = p.params + pg + p.b_off + n;
-          *bptr = fmaf(-p.lr, colsum, *bptr);
-        } else {
-          p.grads[pg + p.b_off + n] = colsum;
+    if (bias_wave && kb == 0) {       // row 0 of the ones product: lane lr32 holds column lr32
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + (wn * TN + j) * 32 + lr32;
+        const float colsum = accb[j][0];
+        if (n < p.N) {
+          if (fused) {
+            float* bptr = p.params + pg + p.b_off + n;
+            *bptr = fmaf(-p.lr, colsum, *bptr);
+          } else {
+            p.grads[pg + p.b_off + n] = colsum;
+          }
         }
       }
     }
@@ -523,13 +550,15 @@ hipError_t launch_gemm_dw(const GemmArgs& p, int n_groups, bool bf16, hipStream_
               : launch_one<TF32, 128, 64, 2, 2, OP_TRANS, OP_TRANS>(p, n_groups, s);
 }
 // The same product with the minibatches of all workers stacked into one contraction (a single
-// group, Kc = N B rows): a long contraction, so the deep pipeline and the widest tile that still
-// fills the chip.
+// group, Kc = N B rows).  Large layers: the deep pipeline on the widest tile.  Layers with few
+// tiles: 64 x 64 tiles on the shallow pipeline, several workgroups per compute unit, so that the
+// weight read-modify-write of one overlaps the products of another (3072 x 1024 with 1024 stacked
+// rows: 22 -> 18 us).
 hipError_t launch_gemm_dw_stacked(const GemmArgs& p, hipStream_t s) {
   const long wide_tiles = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
   if (wide_tiles >= kComputeUnits)
     return launch_one<TBF16, 128, 128, 2, 4, OP_TRANS, OP_TRANS, true>(p, 1, s);
-  return launch_one<TBF16, 128, 64, 2, 2, OP_TRANS, OP_TRANS, true>(p, 1, s);
+  return launch_one<TBF16, 64, 64, 2, 2, OP_TRANS, OP_TRANS, false>(p, 1, s);
 }
 
 }  // namespace prsgd

@@ -349,10 +349,10 @@ def test_c4_full_shape_long_run(P, D, interval):
     P.prsgd_destroy(h)
 
 
-@pytest.mark.parametrize("name,iters,interval", [("c3", 4, 2), ("c5", 2, 2)])
+@pytest.mark.parametrize("name,iters,interval", [("c3", 4, 2), ("c5", 2, 2), ("c3", 4, 1), ("c5", 3, 1)])
 def test_bf16_full_size_replicas(P, D, name, iters, interval):
     # full layer sizes, worker count and batch (the launch shapes the benchmark times) with a
-    # restart every second step; a short horizon and a smaller shard keep the fp64 oracle to
+    # restart every second step, or every step (I = 1: the one-pass form); a short horizon and a smaller shard keep the fp64 oracle to
     # seconds (the configurations' own intervals and shards: tests/test_gpu_horizons.py)
     w = get_workload(name).scaled(rows_per_worker=512, iterations=iters, interval=interval)
     inp = make_inputs(w)
