@@ -33,7 +33,7 @@ KERNEL_SYMBOL = {
     "gemm_dx": "grouped_gemm_kernel<.., OP_CONTIG, OP_CONTIG>",
     "gemm_dw": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS>",
     "gemm_bwd": "grouped_bwd_full_kernel (grouped_bwd_kernel for layers with partial tiles)",
-    "softmax_xent": "softmax_xent_kernel",
+    "softmax_xent": "softmax_xent_kernel (loss head + row gather of the next iteration)",
     "sgd_update": "update_kernel",
     "average": "average_kernel (restart_small_kernel<.., true> when N >= 8 and a replica has fewer "
                "than 262144 floats)",
@@ -82,7 +82,9 @@ def algorithmic_work(w, shared_weights=False):
     out["gemm_fwd"] = {"bytes": fwd_b, "flops": fwd_f}
     out["gemm_dx"] = {"bytes": dx_b, "flops": dx_f}
     out["gemm_dw"] = {"bytes": dw_b, "flops": dw_f}
-    out["softmax_xent"] = {"bytes": n * b * dims[-1] * (4 + es), "flops": 0}
+    # the loss-head launch also gathers the next iteration's minibatch (the stand-alone gather only
+    # runs when no draw is waiting: the first iteration of a run)
+    out["softmax_xent"] = {"bytes": n * b * dims[-1] * (4 + es) + out["gather"]["bytes"], "flops": 0}
     out["sgd_update"] = {"bytes": n * m * (12 + mom + shadow), "flops": (2 + (2 if mom else 0)) * n * m}
     # fused epoch kernel (one launch = `interval` iterations): per iteration the gathered rows and
     # all three products; the weights cross HBM once per launch (read + write), amortised here

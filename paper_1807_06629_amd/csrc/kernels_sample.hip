@@ -4,6 +4,8 @@
 // across workers and iterations.  Here worker i draws B rows of its own shard uniformly with
 // replacement; slot j of iteration t is a pure function of (seed, i, t, j) through
 // Philox4x32-10, so the stream needs no state and can be replayed from any t.
+#include <cstring>
+
 #include "prsgd_internal.h"
 
 namespace prsgd {
@@ -16,19 +18,15 @@ static int ilog2(long n) {
 
 // One workgroup per (slot j, worker i): draw the row, copy it into the batch buffer.
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void gather_kernel(
-    const float* __restrict__ features, const int32_t* __restrict__ labels, void* __restrict__ xb,
-    int32_t* __restrict__ yb, int32_t* __restrict__ idx, int batch, int d0, int ld0, long rows,
-    int log2n, uint64_t seed, uint64_t t, const int* __restrict__ worker_steps, int step) {
-  const int j = blockIdx.x, i = blockIdx.y;
-  if (worker_steps != nullptr && step >= worker_steps[i]) return;
-  const int32_t row = sample_row(seed, (uint32_t)i, t, (uint32_t)j, log2n);
-  const size_t slot = (size_t)i * batch + j;
+__device__ __forceinline__ void gather_row(const GatherArgs& a, int j, int i) {
+  const int32_t row = sample_row(a.seed, (uint32_t)i, a.t, (uint32_t)j, a.log2n);
+  const size_t slot = (size_t)i * a.batch + j;
   if (threadIdx.x == 0) {
-    idx[slot] = row;
-    yb[slot] = labels[(size_t)i * rows + row];
+    a.idx[slot] = row;
+    a.yb[slot] = a.labels[(size_t)i * a.rows + row];
   }
-  const float* src = features + ((size_t)i * rows + row) * d0;
+  const int d0 = a.d0, ld0 = a.ld0;
+  const float* src = a.features + ((size_t)i * a.rows + row) * d0;
   if ((d0 & 3) == 0) {
     const float4* src4 = reinterpret_cast<const float4*>(src);
     for (int c = threadIdx.x; c < d0 / 4; c += kThreads) {
@@ -37,17 +35,25 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(
         uint2 h;
         h.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
         h.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
-        reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(xb) + slot * ld0)[c] = h;
+        reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.xb) + slot * ld0)[c] = h;
       } else {
-        reinterpret_cast<float4*>(reinterpret_cast<float*>(xb) + slot * ld0)[c] = v;
+        reinterpret_cast<float4*>(reinterpret_cast<float*>(a.xb) + slot * ld0)[c] = v;
       }
     }
   } else {
     for (int c = threadIdx.x; c < d0; c += kThreads) {
-      if (BF16) reinterpret_cast<uint16_t*>(xb)[slot * ld0 + c] = f32_to_bf16_rne(src[c]);
-      else reinterpret_cast<float*>(xb)[slot * ld0 + c] = src[c];
+      if (BF16) reinterpret_cast<uint16_t*>(a.xb)[slot * ld0 + c] = f32_to_bf16_rne(src[c]);
+      else reinterpret_cast<float*>(a.xb)[slot * ld0 + c] = src[c];
     }
   }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void gather_kernel(GatherArgs a, const int* __restrict__ worker_steps,
+                                                          int step) {
+  const int j = blockIdx.x, i = blockIdx.y;
+  if (worker_steps != nullptr && step >= worker_steps[i]) return;
+  gather_row<BF16>(a, j, i);
 }
 
 __global__ __launch_bounds__(kThreads) void sample_indices_kernel(int32_t* __restrict__ out,
@@ -63,15 +69,22 @@ __global__ __launch_bounds__(kThreads) void sample_indices_kernel(int32_t* __res
   }
 }
 
-// Softmax cross-entropy head: one wavefront per minibatch row (4 rows per workgroup).
+// Softmax cross-entropy head: one wavefront per minibatch row (4 rows per workgroup).  The same
+// launch can carry the row gather of the next iteration in extra workgroups.
 //   row_loss[b] = -log softmax(z_b)[c_b],   delta = (softmax(z) - onehot(c)) / B
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
     const float* __restrict__ logits, int n_parts, long part_stride, const float* __restrict__ bias,
     long bias_gs, const int32_t* __restrict__ yb, void* __restrict__ delta,
     float* __restrict__ row_loss, int batch, int n_classes, int ldc,
-    const int* __restrict__ worker_steps, int step) {
+    const int* __restrict__ worker_steps, int step, int head_blocks, GatherArgs next) {
   const int g = blockIdx.y;
+  // workgroups beyond the loss head's own: the minibatch draw of the NEXT iteration, which depends
+  // on nothing this iteration computes (zeta_i^t is a function of seed, i, t and the slot alone)
+  if ((int)blockIdx.x >= head_blocks) {
+    gather_row<BF16>(next, (int)blockIdx.x - head_blocks, g);
+    return;
+  }
   if (worker_steps != nullptr && step >= worker_steps[g]) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.x * (kThreads / kWave) + wave;
@@ -154,18 +167,21 @@ __global__ void loss_mean_kernel(const float* __restrict__ row_loss, float* __re
   losses[g] = s / (float)batch;
 }
 
-hipError_t launch_gather(const float* features, const int32_t* labels, void* xb, int32_t* yb,
-                         int32_t* idx, int n_workers, int batch, int d0, int ld0, long rows,
-                         uint64_t seed, int64_t t, bool bf16, const int* worker_steps, int step,
+hipError_t launch_gather(const GatherArgs& a, int n_workers, bool bf16, const int* worker_steps, int step,
                          hipStream_t s) {
-  dim3 grid(batch, n_workers);
-  if (bf16)
-    hipLaunchKernelGGL(gather_kernel<true>, grid, dim3(kThreads), 0, s, features, labels, xb, yb, idx,
-                       batch, d0, ld0, rows, ilog2(rows), seed, (uint64_t)t, worker_steps, step);
-  else
-    hipLaunchKernelGGL(gather_kernel<false>, grid, dim3(kThreads), 0, s, features, labels, xb, yb, idx,
-                       batch, d0, ld0, rows, ilog2(rows), seed, (uint64_t)t, worker_steps, step);
+  dim3 grid(a.batch, n_workers);
+  if (bf16) hipLaunchKernelGGL(gather_kernel<true>, grid, dim3(kThreads), 0, s, a, worker_steps, step);
+  else hipLaunchKernelGGL(gather_kernel<false>, grid, dim3(kThreads), 0, s, a, worker_steps, step);
   return hipGetLastError();
+}
+
+GatherArgs gather_args(const float* features, const int32_t* labels, void* xb, int32_t* yb, int32_t* idx,
+                       int batch, int d0, int ld0, long rows, uint64_t seed, int64_t t) {
+  GatherArgs a;
+  a.features = features; a.labels = labels; a.xb = xb; a.yb = yb; a.idx = idx;
+  a.batch = batch; a.d0 = d0; a.ld0 = ld0; a.rows = rows; a.log2n = ilog2(rows);
+  a.seed = seed; a.t = (uint64_t)t;
+  return a;
 }
 
 hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long rows, int64_t t_first,
@@ -182,14 +198,20 @@ hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long r
 hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_stride, const float* bias,
                                long bias_gs, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
-                               const int* worker_steps, int step, hipStream_t s) {
-  dim3 grid((batch + kThreads / kWave - 1) / (kThreads / kWave), n_workers);
+                               const int* worker_steps, int step, const GatherArgs* next, hipStream_t s) {
+  const int head_blocks = (batch + kThreads / kWave - 1) / (kThreads / kWave);
+  GatherArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  if (next != nullptr) ga = *next;
+  dim3 grid(head_blocks + (next != nullptr ? next->batch : 0), n_workers);
   if (bf16)
     hipLaunchKernelGGL(softmax_xent_kernel<true>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
-                       bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step);
+                       bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step,
+                       head_blocks, ga);
   else
     hipLaunchKernelGGL(softmax_xent_kernel<false>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
-                       bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step);
+                       bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step,
+                       head_blocks, ga);
   return hipGetLastError();
 }
 

@@ -32,7 +32,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local char g_init_error[256] = "";
 
 struct Carve {
-  size_t xb = 0, yb = 0, idx = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, mean_shadow = 0, steps = 0, vel = 0;
+  size_t xb = 0, yb = 0, idx = 0, xb2 = 0, yb2 = 0, idx2 = 0, logits = 0, losses = 0, row_loss = 0, part = 0, sync = 0, shadow = 0, grads = 0, mean = 0, mean_shadow = 0, steps = 0, vel = 0;
   size_t h[PRSGD_MAX_DIMS] = {0}, delta[PRSGD_MAX_DIMS] = {0};
   size_t total = 0;
 };
@@ -119,6 +119,10 @@ void build_carve(const prsgd_config* c_in, const Layout& lo, Carve* cv) {
     cv->yb = take(n * b * 4);
     cv->row_loss = take(n * b * 4);
     cv->xb = take(n * b * lo.ld[0] * es);
+    // second set: the next iteration's minibatch is gathered while the current one is in use
+    cv->xb2 = take(n * b * lo.ld[0] * es);
+    cv->yb2 = take(n * b * 4);
+    cv->idx2 = take(n * b * 4);
     for (int l = 1; l < L; ++l) {
       cv->h[l] = take(n * b * lo.ld[l] * es);
       cv->delta[l] = take(n * b * lo.ld[l] * es);
@@ -170,6 +174,10 @@ struct prsgd_ctx {
   float* params;
   char* ws;
   int64_t t;
+  // two minibatch buffer sets (layer-wise MLP path): batch_t[k] is the iteration whose draw set k
+  // holds for ALL workers (-1: none), batch_cur the set of the last local iteration
+  int64_t batch_t[2];
+  int batch_cur;
   float lr;
   char err[256];
   // profiling
@@ -185,6 +193,9 @@ struct prsgd_ctx {
                                       // static ones of prsgd_init_static
 
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  void* xb(int k) const { return at<void>(k ? cv.xb2 : cv.xb); }
+  int32_t* yb(int k) const { return at<int32_t>(k ? cv.yb2 : cv.yb); }
+  int32_t* idx(int k) const { return at<int32_t>(k ? cv.idx2 : cv.idx); }
   uint16_t* shadow() const { return bf16 ? at<uint16_t>(cv.shadow) : nullptr; }
   float* mean() const { return at<float>(cv.mean); }
   float* velocity() const { return cfg.momentum != 0.0f ? at<float>(cv.vel) : nullptr; }
@@ -271,11 +282,21 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   const bool bf16 = ctx->bf16;
   hipStream_t s = ctx->stream;
 
-  LAUNCH(ctx, KK_GATHER,
-         launch_gather(ctx->features, reinterpret_cast<const int32_t*>(ctx->targets),
-                       ctx->at<void>(cv.xb), ctx->at<int32_t>(cv.yb), ctx->at<int32_t>(cv.idx), N, B,
-                       lo.d[0], lo.ld[0], (long)c.rows_per_worker, c.seed, t, bf16, worker_steps, step,
-                       s));
+  // The minibatch of iteration t: already there when the previous iteration's loss-head launch
+  // drew it (below); otherwise gathered now.  A masked draw (Algorithm 3) is never reused.
+  auto batch_args = [&](int k, int64_t tt) {
+    return gather_args(ctx->features, reinterpret_cast<const int32_t*>(ctx->targets), ctx->xb(k), ctx->yb(k),
+                       ctx->idx(k), B, lo.d[0], lo.ld[0], (long)c.rows_per_worker, c.seed, tt);
+  };
+  int bk = -1;
+  if (worker_steps == nullptr) bk = ctx->batch_t[0] == t ? 0 : ctx->batch_t[1] == t ? 1 : -1;
+  if (bk < 0) {
+    bk = ctx->batch_cur;
+    ctx->batch_t[bk] = -1;
+    LAUNCH(ctx, KK_GATHER, launch_gather(batch_args(bk, t), N, bf16, worker_steps, step, s));
+    if (worker_steps == nullptr) ctx->batch_t[bk] = t;
+  }
+  ctx->batch_cur = bk;
 
   GemmArgs base;
   memset(&base, 0, sizeof(base));
@@ -290,7 +311,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   base.step = step;
 
   auto act_in = [&](int l) -> const void* {   // H_l as stored (l = 0: the gathered batch)
-    return l == 0 ? ctx->at<void>(cv.xb) : ctx->at<void>(cv.h[l]);
+    return l == 0 ? ctx->xb(bk) : ctx->at<void>(cv.h[l]);
   };
   const bool fused_bwd = bf16 && c.fused_update && bwd_fused_supported(B);
   // Right after a restart every worker starts from the shared node average (stride 0); only
@@ -329,12 +350,17 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
     LAUNCH(ctx, KK_FWD, launch_gemm_fwd(p, N, bf16, s));
   }
 
+  // the loss-head launch also draws the minibatch of iteration t + 1 into the other buffer set
+  const bool prefetch = worker_steps == nullptr;
+  GatherArgs next_batch = batch_args(bk ^ 1, t + 1);
+  if (prefetch) ctx->batch_t[bk ^ 1] = -1;
   LAUNCH(ctx, KK_LOSS,
          launch_softmax_xent(ctx->at<float>(cv.logits), logit_parts, logit_part_stride,
                              logit_parts > 1 ? ctx->src() + lo.b_off[L - 1] : nullptr, ctx->src_stride(),
-                             ctx->at<int32_t>(cv.yb),
+                             ctx->yb(bk),
                              ctx->at<void>(cv.delta[L]), ctx->at<float>(cv.row_loss), N, B, lo.d[L],
-                             lo.ld[L], bf16, worker_steps, step, s));
+                             lo.ld[L], bf16, worker_steps, step, prefetch ? &next_batch : nullptr, s));
+  if (prefetch) ctx->batch_t[bk ^ 1] = t + 1;
 
   if (fuse_average) {
     // eq. (3) from the common point and eq. (2) in one pass over ybar, layer by layer from the
@@ -629,6 +655,8 @@ int init_common(const prsgd_config* cfg, const float* x0_host, const void* featu
   ctx->params = reinterpret_cast<float*>(params_dev);
   ctx->ws = reinterpret_cast<char*>(workspace_dev);
   ctx->t = 0;
+  ctx->batch_t[0] = ctx->batch_t[1] = -1;
+  ctx->batch_cur = 0;
   ctx->lazy_restart = true;
   ctx->at_mean = false;
   ctx->poisoned = false;
@@ -989,7 +1017,8 @@ int prsgd_read_indices(prsgd_ctx* ctx, int32_t* out_host) {
   const int arc = check_fused2_abort(ctx);
   if (arc != PRSGD_OK) return arc;
   const size_t bytes = sizeof(int32_t) * (size_t)ctx->cfg.n_workers * ctx->cfg.batch;
-  hipError_t e = hipMemcpyAsync(out_host, ctx->at<int32_t>(ctx->cv.idx), bytes, hipMemcpyDeviceToHost,
+  // the layer-wise MLP path alternates between two buffer sets; the others only use the first
+  hipError_t e = hipMemcpyAsync(out_host, ctx->idx(ctx->batch_cur), bytes, hipMemcpyDeviceToHost,
                                 ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_read_indices");

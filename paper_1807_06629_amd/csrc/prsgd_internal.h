@@ -125,16 +125,24 @@ hipError_t launch_gemm_dx(const GemmArgs& p, int n_groups, bool bf16, hipStream_
 hipError_t launch_gemm_dw_stacked(const GemmArgs& p, hipStream_t s);   // bf16 operands, one group
 hipError_t launch_gemm_dw(const GemmArgs& p, int n_groups, bool bf16, hipStream_t s);
 
-hipError_t launch_gather(const float* features, const int32_t* labels, void* xb, int32_t* yb,
-                         int32_t* idx, int n_workers, int batch, int d0, int ld0, long rows,
-                         uint64_t seed, int64_t t, bool bf16, const int* worker_steps, int step,
+// Minibatch draw of iteration t: rows of the workers' shards copied into the batch buffer.
+struct GatherArgs {
+  const float* features; const int32_t* labels;
+  void* xb; int32_t* yb; int32_t* idx;        // batch rows [N][B][ld0], labels and row indices [N][B]
+  int batch, d0, ld0; long rows; int log2n;
+  uint64_t seed, t;
+};
+GatherArgs gather_args(const float* features, const int32_t* labels, void* xb, int32_t* yb, int32_t* idx,
+                       int batch, int d0, int ld0, long rows, uint64_t seed, int64_t t);
+hipError_t launch_gather(const GatherArgs& a, int n_workers, bool bf16, const int* worker_steps, int step,
                          hipStream_t s);
 hipError_t launch_sample_indices(uint64_t seed, int n_workers, int batch, long rows, int64_t t_first,
                                  int n_steps, int32_t* out, hipStream_t s);
+// next != nullptr: the launch also gathers that minibatch (all workers, no step mask)
 hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_stride, const float* bias,
                                long bias_gs, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
-                               const int* worker_steps, int step, hipStream_t s);
+                               const int* worker_steps, int step, const GatherArgs* next, hipStream_t s);
 hipError_t launch_loss_mean(const float* row_loss, float* losses, int n_workers, int batch,
                             hipStream_t s);
 
