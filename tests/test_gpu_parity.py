@@ -89,6 +89,45 @@ def test_local_step_uses_the_same_rows_as_the_stateless_stream(P, D):
     P.prsgd_destroy(h)
 
 
+def test_draw_ahead_follows_the_iteration_counter(P, D):
+    """The layer-wise path draws the minibatch of iteration t + 1 during iteration t; a changed
+    counter, or a heterogeneous epoch (masked draws) in between, must not let a stale draw through.
+    The draw is a pure function of (seed, worker, t, slot): the row indices tell."""
+    w = small_mlp(dims=(40, 24, 16, 6), batch=6, n_workers=3, rows_per_worker=128)   # per-layer kernels
+    inp = inputs_for(w)
+    h = _open(D, w, inp)
+
+    def rows_of(t):
+        return np.stack([oracle.sample_rows(w.index_seed, i, t, w.batch, w.rows_per_worker)
+                         for i in range(w.n_workers)])
+
+    P.prsgd_local_steps(h, 1)
+    assert np.array_equal(P.prsgd_read_indices(h), rows_of(1))
+    P.prsgd_local_steps(h, 2)                          # both taken from draws made ahead
+    assert np.array_equal(P.prsgd_read_indices(h), rows_of(3))
+    P.prsgd_set_iteration(h, 40)                       # the waiting draw (t = 4) is not t = 41
+    P.prsgd_local_steps(h, 1)
+    assert np.array_equal(P.prsgd_read_indices(h), rows_of(41))
+    P.prsgd_set_iteration(h, 41)                       # same counter again: the draw ahead is t = 42
+    P.prsgd_local_steps(h, 1)
+    assert np.array_equal(P.prsgd_read_indices(h), rows_of(42))
+    P.prsgd_local_steps_hetero(h, [2, 0, 1])           # t = 43, 44; worker 1 draws nothing
+    got = P.prsgd_read_indices(h)
+    assert np.array_equal(got[0], rows_of(44)[0])
+    P.prsgd_local_steps(h, 1)                          # t = 45, complete again
+    assert np.array_equal(P.prsgd_read_indices(h), rows_of(45))
+    P.prsgd_destroy(h)
+    # the same sequence of counters gives the same parameters as stepping without any jump
+    a, b = _open(D, w, inp), _open(D, w, inp)
+    P.prsgd_local_steps(a, 5)
+    for _ in range(5):
+        P.prsgd_set_iteration(b, P.prsgd_iteration(b))
+        P.prsgd_local_steps(b, 1)
+    assert np.array_equal(D.read_all(a), D.read_all(b))
+    P.prsgd_destroy(a)
+    P.prsgd_destroy(b)
+
+
 # --------------------------------------------------------------------------- least squares
 def test_c1_least_squares_full_run(P, D):
     w = get_workload("c1")
