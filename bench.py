@@ -339,12 +339,15 @@ def main() -> int:
     one_pass = (w.interval == 1 and w.model == "mlp" and w.gemm_dtype == "bf16" and not args.unfused
                 and not args.eager_restart and w.momentum == 0.0 and w.batch <= 128)
     work = algorithmic_work(w, shared_weights=one_pass)
+    prof_key = w.name + ("_I1" if one_pass else "")      # counter readings are kept per launch pattern
     kernels = {}
     for s in stats:
         per_iter = work.get(s["name"], {"bytes": 0, "flops": 0})
         calls = prof_steps if s["name"] not in ("average", "restart_mean") else max(1, prof_steps // w.interval)
         if s["name"] in ("lsq_steps", "mlp2_epoch"):
             calls = prof_steps                        # one launch covers several iterations
+        if s["name"] == "gather":
+            calls = s["launches"]                     # only when no draw made ahead is waiting
         tot_bytes, tot_flops = per_iter["bytes"] * calls, per_iter["flops"] * calls
         sec = s["total_ms"] * 1e-3
         kernels[s["name"]] = {
@@ -373,8 +376,8 @@ def main() -> int:
                         "frac_of_peak": kd["TFLOPs"] / peak_tf,
                         "flop_per_byte": ai,
                         "ceiling_frac_at_hbm_peak": min(1.0, ai * HBM_PEAK_GBPS * 1e9 / (peak_tf * 1e12)),
-                        "busy_counters": measured_counters(w.name, dom)}
-    roof.update({"traffic": measured_traffic(w.name, dom), "kernel": dom, "symbol": KERNEL_SYMBOL.get(dom, dom),
+                        "busy_counters": measured_counters(prof_key, dom)}
+    roof.update({"traffic": measured_traffic(prof_key, dom), "kernel": dom, "symbol": KERNEL_SYMBOL.get(dom, dom),
                  "avg_launch_us": kd["avg_us"], "launches_timed": kd["launches"],
                  "algorithmic_bytes_per_launch": kd["bytes_per_launch"],
                  "algorithmic_flops_per_launch": kd["flops_per_launch"]})

@@ -41,7 +41,11 @@ struct TBF16 {
 #endif
   static constexpr int BK = PRSGD_BF16_BK;
   static constexpr int PADC = 8;
-  static constexpr int PADT = 16;    // 4 consecutive k rows of a transpose read hit distinct banks
+  // A transpose read (ds_read_b64_tr_b16) is served 32 lanes at a time: 4 consecutive contraction rows
+  // times 16 dwords each.  With a row stride of 16 dwords modulo 32 (32 bf16 modulo 64) they fall on
+  // 64 distinct banks; the earlier padding of 16 lost 17 % (one transposed operand) to 37 % (two) of the
+  // LDS cycles to bank conflicts, this one none (SQ_LDS_BANK_CONFLICT).
+  static constexpr int PADT = 32;
   static constexpr bool kBf16 = true;
 };
 
