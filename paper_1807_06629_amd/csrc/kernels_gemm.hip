@@ -237,23 +237,24 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
   constexpr bool kIsDw = (AKIND == OP_TRANS && BKIND == OP_TRANS);   // weight-gradient product
   const bool fused = kIsDw && (p.epi == EPI_DW_FUSED);
 
-  // Weight-update epilogue: start streaming the old weights now, they are not needed until
-  // the products are done.
-  float w_old[kIsDw ? TM : 1][kIsDw ? TN : 1][16];
+  // Weight-update epilogue: the output tile leaves through LDS in row-major order, one 16-byte
+  // vector per lane (EV vectors per thread).  Start streaming the old weights in that layout now,
+  // they are not needed until the products are done.
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  constexpr int SC = BN + 8;                               // LDS row stride of the output tile (floats)
+  constexpr int VPR_C = BN / 4, ROWS_PER_PASS = NTHR / VPR_C, EV = kIsDw ? BM / ROWS_PER_PASS : 1;
+  static_assert(!kIsDw || (NTHR % VPR_C == 0 && BM % ROWS_PER_PASS == 0), "output tile must split evenly");
+  const int e_row = tid / VPR_C, e_col = 4 * (tid % VPR_C);
+  f32x4_t w_old[EV];
   if constexpr (kIsDw) if (fused) {
     const float* wbase = p.params + pg + p.w_off;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
-          const int n = n0 + (wn * TN + j) * 32 + lr32;
-          const bool ok = m < p.M && n < p.N;
-          const float* wp = wbase + (ok ? (size_t)m * p.ldw + n : (size_t)0);
-          w_old[i][j][v] = p.streaming ? __builtin_nontemporal_load(wp) : *wp;
-        }
+    for (int q = 0; q < EV; ++q) {
+      const int m = m0 + q * ROWS_PER_PASS + e_row, n = n0 + e_col;
+      const bool ok = m < p.M && n < p.N;
+      const f32x4_t* wp = reinterpret_cast<const f32x4_t*>(wbase + (ok ? (size_t)m * p.ldw + n : (size_t)0));
+      w_old[q] = p.streaming ? __builtin_nontemporal_load(wp) : *wp;
+    }
   }
 
   f32x16_t acc[TM][TN];
@@ -386,31 +387,47 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_kernel(GemmArgs p) 
   // ---- epilogue: accumulator element v of lane (lr32, kb) is C[8*(v/4) + 4*kb + v%4][lr32] ----
   if constexpr (kIsDw) {
     float* wbase = (fused ? p.params : p.grads) + pg + p.w_off;
+    // accumulators -> LDS (the operand stages are free now) -> row-major 16-byte accesses
+    float* c_lds = reinterpret_cast<float*>(smem);
+    __syncthreads();                                       // every wavefront is done with the last tile
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
-          const int n = n0 + (wn * TN + j) * 32 + lr32;
-          if (m < p.M && n < p.N) {
-            const size_t off = (size_t)m * p.ldw + n;
-            if (fused) {
-              const float w_new = fmaf(-p.lr, acc[i][j][v], w_old[i][j][v]);
-              if (p.streaming) {
-                __builtin_nontemporal_store(w_new, wbase + off);
-                if (p.shadow != nullptr)
-                  __builtin_nontemporal_store(f32_to_bf16_rne(w_new), p.shadow + pg + p.w_off + off);
-              } else {
-                wbase[off] = w_new;
-                if (p.shadow != nullptr) p.shadow[pg + p.w_off + off] = f32_to_bf16_rne(w_new);
-              }
-            } else {
-              wbase[off] = acc[i][j][v];
-            }
+        for (int v = 0; v < 16; ++v)
+          c_lds[((wm * TM + i) * 32 + 8 * (v / 4) + 4 * kb + (v % 4)) * SC + (wn * TN + j) * 32 + lr32] =
+              acc[i][j][v];
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < EV; ++q) {
+      const int r = q * ROWS_PER_PASS + e_row;
+      const int m = m0 + r, n = n0 + e_col;
+      if (m < p.M && n < p.N) {
+        const f32x4_t g = *reinterpret_cast<const f32x4_t*>(c_lds + r * SC + e_col);
+        const size_t off = (size_t)m * p.ldw + n;
+        if (fused) {
+          f32x4_t w = w_old[q];
+          w.x = fmaf(-p.lr, g.x, w.x);
+          w.y = fmaf(-p.lr, g.y, w.y);
+          w.z = fmaf(-p.lr, g.z, w.z);
+          w.w = fmaf(-p.lr, g.w, w.w);
+          typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+          const u32x2_t hv = {(uint32_t)f32_to_bf16_rne(w.x) | ((uint32_t)f32_to_bf16_rne(w.y) << 16),
+                              (uint32_t)f32_to_bf16_rne(w.z) | ((uint32_t)f32_to_bf16_rne(w.w) << 16)};
+          if (p.streaming) {
+            __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(wbase + off));
+            if (p.shadow != nullptr)
+              __builtin_nontemporal_store(hv, reinterpret_cast<u32x2_t*>(p.shadow + pg + p.w_off + off));
+          } else {
+            *reinterpret_cast<f32x4_t*>(wbase + off) = w;
+            if (p.shadow != nullptr) *reinterpret_cast<u32x2_t*>(p.shadow + pg + p.w_off + off) = hv;
           }
+        } else {
+          *reinterpret_cast<f32x4_t*>(wbase + off) = g;
         }
+      }
+    }
     if (bias_wave && kb == 0) {       // row 0 of the ones product: lane lr32 holds column lr32
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -473,8 +490,12 @@ static hipError_t launch_one(GemmArgs p, int n_groups, hipStream_t s) {
   if (p.M <= 0 || p.N <= 0 || n_groups <= 0) return hipSuccess;
   using E = typename T::elem;
   constexpr size_t kStages = DEEP ? 2 : 1;
-  constexpr size_t kLds =
+  constexpr bool kIsDw = (AKIND == OP_TRANS && BKIND == OP_TRANS);
+  constexpr size_t kStageBytes =
       kStages * sizeof(E) * (TileShape<T, BM, AKIND>::kElems + TileShape<T, BN, BKIND>::kElems);
+  // the weight-gradient product parks its fp32 output tile [BM][BN + 8] in the same memory
+  constexpr size_t kOutBytes = kIsDw ? sizeof(float) * BM * (BN + 8) : 0;
+  constexpr size_t kLds = kStageBytes > kOutBytes ? kStageBytes : kOutBytes;
   auto kernel = grouped_gemm_kernel<T, BM, BN, WM, WN, AKIND, BKIND, DEEP>;
   // double-buffered tiles can exceed the 64 KB default; setting the limit twice is harmless
   static std::atomic<bool> configured{false};
