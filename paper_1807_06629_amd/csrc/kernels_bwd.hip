@@ -622,6 +622,17 @@ hipError_t launch_bwd_fused(const BwdArgs& p, hipStream_t s) {
   // 272 us against 298 us on 4096 x 4096 when the kernel runs alone in a loop, but 297 us against
   // 283 us inside the real step: not kept.
   if (bwd_full_applies(p, mb, 2)) PRSGD_BWD_PICK(launch_bwd_full2);
+  // A layer whose rows are padded to whole column tiles (ld a multiple of 64, less than one tile of
+  // padding) is walked over its padded width: the padding columns of W_l, D_l and b_l are zero,
+  // their gradient is zero, and the update leaves them zero.
+  if ((p.Nn % BN) != 0 && (p.ldw % BN) == 0 && p.ldw - p.Nn < BN && p.ldd == p.ldw) {
+    BwdArgs padded = p;
+    padded.Nn = p.ldw;
+    if (bwd_full_applies(padded, mb, 2)) {
+      const BwdArgs& p = padded;
+      PRSGD_BWD_PICK(launch_bwd_full2);
+    }
+  }
   PRSGD_BWD_PICK(launch_bwd_one);
 #undef PRSGD_BWD_PICK
 }

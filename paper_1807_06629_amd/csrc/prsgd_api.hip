@@ -69,7 +69,9 @@ bool build_layout(const prsgd_config* c, Layout* lo, char* err, size_t errn) {
   for (int l = 0; l < c->n_dims; ++l) {
     if (c->dims[l] < 1 || c->dims[l] > (1 << 20)) return fail("layer width out of range");
     lo->d[l] = c->dims[l];
-    lo->ld[l] = (int)align_up((size_t)c->dims[l], 8);
+    // rows of 8 elements; wide layers (>= 512) are padded to whole 64-column tiles so that the
+    // whole-tile kernels apply to them (the padding columns hold zeros and stay zero)
+    lo->ld[l] = (int)align_up((size_t)c->dims[l], (l > 0 && c->dims[l] >= 512) ? 64 : 8);
   }
   for (int l = 1; l < c->n_dims; ++l) {
     lo->w_off[l - 1] = off;
