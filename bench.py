@@ -41,16 +41,19 @@ KERNEL_SYMBOL = {
                     "fewer than 262144 floats)",
     "lsq_steps": "lsq_steps_staged_kernel (lsq_steps_kernel for shapes it does not take)",
     "mlp2_epoch": "mlp2_epoch_kernel",
+    "gemm_bwd_first": "bwd_first_fwd_kernel (layer 1: backward step + next forward product)",
     "step_mean": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS, true> (the minibatches of all workers "
                  "stacked into one contraction)",
 }
 
 
-def algorithmic_work(w, shared_weights=False):
+def algorithmic_work(w, shared_weights=False, first_fused=False):
     """Algorithmic HBM bytes and flops of ONE iteration, per kernel label (all launches of
     that label in the iteration summed), plus those of one restart average.  shared_weights:
     every iteration starts from the node average (I = 1, one-pass form), so the forward and
-    backward-data products read one weight matrix per layer instead of one per worker."""
+    backward-data products read one weight matrix per layer instead of one per worker.
+    first_fused: the first layer's backward kernel also runs the next forward product of that
+    layer (label gemm_bwd_first), so gemm_fwd and gemm_bwd cover the layers above it."""
     n, b = w.n_workers, w.batch
     nw = 1 if shared_weights else n
     out = {}
@@ -78,6 +81,17 @@ def algorithmic_work(w, shared_weights=False):
     bwd_b = sum(n * (di * do * (10 + mom) + b * (di + do) * 2) for di, do in layers) + \
         sum(n * b * di * 2 for di, do in layers[1:])
     out["gemm_bwd"] = {"bytes": bwd_b, "flops": dw_f + dx_f}
+    # first layer, backward + next forward in one pass: master read + write, shadow write, the
+    # minibatches of both iterations, the delta panel, the next activation; both products
+    d0, d1 = layers[0]
+    first_b = n * (d0 * d1 * (10 + mom) + b * (2 * d0 + 2 * d1) * 2)
+    first_f = 4 * n * b * d0 * d1
+    out["gemm_bwd_first"] = {"bytes": first_b, "flops": first_f}
+    if first_fused:
+        l1_bwd_b = n * (d0 * d1 * (10 + mom) + b * (d0 + d1) * 2)
+        l1_fwd_b = nw * d0 * d1 * es + n * (b * d0 * es + b * d1 * es)
+        out["gemm_bwd"] = {"bytes": bwd_b - l1_bwd_b, "flops": dw_f + dx_f - 2 * n * b * d0 * d1}
+        fwd_b, fwd_f = fwd_b - l1_fwd_b, fwd_f - 2 * n * b * d0 * d1
     out["gather"] = {"bytes": n * b * dims[0] * (4 + es), "flops": 0}
     out["gemm_fwd"] = {"bytes": fwd_b, "flops": fwd_f}
     out["gemm_dx"] = {"bytes": dx_b, "flops": dx_f}
@@ -250,6 +264,8 @@ def main() -> int:
     ap.add_argument("--unfused", action="store_true", help="separate elementwise update kernel")
     ap.add_argument("--eager-restart", action="store_true",
                     help="restart with the averaging kernel that overwrites every replica at once")
+    ap.add_argument("--separate-first-layer", action="store_true",
+                    help="first layer: backward kernel and next forward product as two launches")
     ap.add_argument("--momentum", type=float, default=None,
                     help="momentum of the local steps (default: the workload's, 0 = eq. 3 as printed)")
     ap.add_argument("--momentum-restart", choices=["keep", "average", "reset"], default=None)
@@ -313,6 +329,8 @@ def main() -> int:
                                   stream=stream)
     if args.eager_restart:
         prsgd.prsgd_set_lazy_restart(h, False)
+    if args.separate_first_layer:
+        prsgd.prsgd_set_first_layer_fusion(h, False)
     torch.cuda.synchronize()
 
     prsgd.prsgd_run(h, warmup, w.interval)
@@ -338,7 +356,8 @@ def main() -> int:
 
     one_pass = (w.interval == 1 and w.model == "mlp" and w.gemm_dtype == "bf16" and not args.unfused
                 and not args.eager_restart and w.momentum == 0.0 and w.batch <= 128)
-    work = algorithmic_work(w, shared_weights=one_pass)
+    first_fused = any(s["name"] == "gemm_bwd_first" for s in stats)
+    work = algorithmic_work(w, shared_weights=one_pass, first_fused=first_fused)
     prof_key = w.name + ("_I1" if one_pass else "")      # counter readings are kept per launch pattern
     kernels = {}
     for s in stats:

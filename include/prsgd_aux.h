@@ -29,6 +29,14 @@ int prsgd_copy_bytes(void* dst_dev, const void* src_dev, size_t bytes, void* hip
  */
 int prsgd_set_epoch_wait_limit(prsgd_ctx* ctx, uint32_t polls);
 
+/*
+ * on = 1 (default): on MLPs with bf16 operands the backward kernel of the first layer also runs the
+ * first forward product of the next local iteration on the weights it writes (the minibatch of
+ * iteration t + 1 is drawn during iteration t), so W_1 crosses HBM once per iteration.  on = 0: two
+ * separate launches.  The results are identical bit for bit; tests compare the two.
+ */
+int prsgd_set_first_layer_fusion(prsgd_ctx* ctx, int32_t on);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ namespace prsgd {
 const char* kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
                                         "sgd_update", "average", "mean",       "broadcast", "lsq_steps",
-                                        "mlp2_epoch", "gemm_bwd", "restart_mean", "step_mean"};
+                                        "mlp2_epoch", "gemm_bwd", "restart_mean", "step_mean", "gemm_bwd_first"};
   return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
 }
 }  // namespace prsgd
@@ -180,6 +180,11 @@ struct prsgd_ctx {
   // holds for ALL workers (-1: none), batch_cur the set of the last local iteration
   int64_t batch_t[2];
   int batch_cur;
+  // first hidden activation computed ahead by the first layer's backward kernel: valid for
+  // iteration h1_t on batch set h1_batch while the replicas are untouched (-1: none)
+  int64_t h1_t;
+  int h1_batch;
+  bool first_fusion;    // let the first layer's backward kernel run the next forward product
   float lr;
   char err[256];
   // profiling
@@ -331,10 +336,15 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   base.bias_src = ctx->src();
   base.bias_gs = ctx->src_stride();
 
-  // forward
+  // forward.  H_1 may already be there: the previous iteration's first-layer backward kernel computes
+  // it from the weights it writes, for this iteration's minibatch
+  const bool h1_ready = fused_bwd && !from_mean && worker_steps == nullptr && !fuse_average && L >= 2 &&
+                        ctx->h1_t == t && ctx->h1_batch == bk;
+  ctx->h1_t = -1;
   int logit_parts = 1;
   const long logit_part_stride = (long)N * B * lo.ld[L];
   for (int l = 1; l <= L; ++l) {
+    if (l == 1 && h1_ready) continue;
     GemmArgs p = base;
     p.a = act_in(l - 1); p.a_gs = (long)B * lo.ld[l - 1]; p.lda = lo.ld[l - 1];
     p.b = bf16 ? (const void*)(reinterpret_cast<const uint16_t*>(wsrc) + lo.w_off[l - 1])
@@ -410,6 +420,16 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
     q.lr = ctx->lr;
     q.vel = ctx->velocity(); q.mu = c.momentum;
     q.worker_steps = worker_steps; q.step = step;
+    if (l == 1 && L >= 2 && ctx->first_fusion && prefetch && ctx->batch_t[bk ^ 1] == t + 1) {
+      q.x_next = reinterpret_cast<const uint16_t*>(ctx->xb(bk ^ 1)); q.x_gs = (long)B * lo.ld[0]; q.ldx = lo.ld[0];
+      q.h_next = ctx->at<uint16_t>(cv.h[1]); q.hn_gs = (long)B * lo.ld[1]; q.ldhn = lo.ld[1];
+      if (bwd_first_fwd_applies(q)) {
+        LAUNCH(ctx, KK_BWD_FIRST, launch_bwd_first_fwd(q, s));
+        ctx->h1_t = t + 1;
+        ctx->h1_batch = bk ^ 1;
+        continue;
+      }
+    }
     LAUNCH(ctx, KK_BWD, launch_bwd_fused(q, s));
   }
   // otherwise: D_{l-1} needs the pre-update W_l, so it runs before layer l's weight kernel
@@ -524,6 +544,7 @@ int check_fused2_abort(prsgd_ctx* ctx) {
 // Writes the node average into every replica (and the bf16 shadow) if the last restart left the
 // replicas stale.
 int materialize(prsgd_ctx* ctx) {
+  ctx->h1_t = -1;
   if (!ctx->at_mean) return PRSGD_OK;
   LAUNCH(ctx, KK_BROADCAST, launch_broadcast(ctx->mean(), ctx->params, ctx->shadow(), ctx->lo.m_pad,
                                              ctx->cfg.n_workers, ctx->stream));
@@ -659,6 +680,9 @@ int init_common(const prsgd_config* cfg, const float* x0_host, const void* featu
   ctx->t = 0;
   ctx->batch_t[0] = ctx->batch_t[1] = -1;
   ctx->batch_cur = 0;
+  ctx->h1_t = -1;
+  ctx->h1_batch = 0;
+  ctx->first_fusion = true;
   ctx->lazy_restart = true;
   ctx->at_mean = false;
   ctx->poisoned = false;
@@ -836,6 +860,7 @@ int prsgd_average(prsgd_ctx* ctx) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (check_poisoned(ctx) != PRSGD_OK) return PRSGD_ESTATE;
   if (ctx->at_mean) return PRSGD_OK;        // all workers already sit at their node average
+  ctx->h1_t = -1;                           // an activation computed ahead belongs to the old points
   if (ctx->velocity() != nullptr && ctx->cfg.momentum_restart != PRSGD_MOM_KEEP) {
     // the paper leaves the momentum buffers at a restart open: average them like the points,
     // or start every epoch without momentum
@@ -945,6 +970,7 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
     }
   }
   ctx->at_mean = false;
+  ctx->h1_t = -1;
   pad_from_dense(ctx, in_host, ctx->host_pad);
   const size_t bytes = sizeof(float) * (size_t)ctx->lo.m_pad;
   hipError_t e;
@@ -1064,6 +1090,13 @@ int prsgd_status(prsgd_ctx* ctx) {
   if (arc != PRSGD_OK) return arc;
   const hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_status");
+  return PRSGD_OK;
+}
+
+int prsgd_set_first_layer_fusion(prsgd_ctx* ctx, int32_t on) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  ctx->first_fusion = on != 0;
+  ctx->h1_t = -1;
   return PRSGD_OK;
 }
 

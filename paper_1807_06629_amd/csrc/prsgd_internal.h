@@ -69,7 +69,7 @@ constexpr int kMaxLogitSplits = 4;
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
-  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_STEP_MEAN, KK_COUNT
+  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_STEP_MEAN, KK_BWD_FIRST, KK_COUNT
 };
 
 // Fused backward step of one layer with bf16 operands (kernels_bwd.hip): weight gradient, local
@@ -88,9 +88,16 @@ struct BwdArgs {
   float lr;
   float* vel; float mu;                         // momentum buffers [N][p_gs] (nullptr = plain SGD)
   const int* worker_steps; int step;            // Algorithm 3 mask (nullptr = all active)
+  // first layer only (kernels_bwd_first.hip): minibatch of the next iteration [N][B][ldx] and
+  // where its first hidden activation goes [N][B][ldhn]
+  const uint16_t* x_next; long x_gs; int ldx;
+  uint16_t* h_next; long hn_gs; int ldhn;
 };
 bool bwd_fused_supported(int batch);
 hipError_t launch_bwd_fused(const BwdArgs& p, hipStream_t s);
+// Layer 1: backward step fused with the next iteration's forward product of that layer.
+bool bwd_first_fwd_applies(const BwdArgs& p);
+hipError_t launch_bwd_first_fwd(const BwdArgs& p, hipStream_t s);
 
 // Epoch kernel for fp32 MLPs with one hidden layer (kernels_fused2.hip).
 struct Fused2Plan {

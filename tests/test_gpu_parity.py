@@ -333,6 +333,45 @@ def test_c3_shape_noniid_reduced(P, D):
     P.prsgd_destroy(sync)
 
 
+@pytest.mark.parametrize("shape", [
+    dict(dims=(256, 128, 64, 10), batch=32, n_workers=3),
+    dict(dims=(384, 192, 10), batch=64, n_workers=8),
+    dict(dims=(512, 64, 72, 12), batch=128, n_workers=2),
+])
+@pytest.mark.parametrize("activation", ["relu", "tanh"])
+def test_first_layer_backward_runs_the_next_forward_product(P, D, shape, activation):
+    """Layers made of whole tiles: the backward kernel of layer 1 also computes H_1 of the next
+    iteration from the weights it writes.  Same bits as the two separate launches, through restarts,
+    a rewritten replica, a moved iteration counter and an Algorithm 3 epoch in between."""
+    w = small_mlp(gemm_dtype="bf16", activation=activation, rows_per_worker=256, interval=3, iterations=8,
+                  **shape)
+    inp = inputs_for(w)
+    outs = []
+    for on in (True, False):
+        h = _open(D, w, inp)
+        P.prsgd_set_first_layer_fusion(h, on)
+        names = _kernel_names(P, h, w.iterations, w.interval)
+        assert ("gemm_bwd_first" in names) == on, names
+        first = (D.read_all(h), P.prsgd_read_loss(h), P.prsgd_read_indices(h))
+        # the activation computed ahead must be dropped when the points or the counter change
+        x1 = P.prsgd_read_params(h, 1)
+        P.prsgd_write_params(h, 1, (x1 * np.float32(0.5)).astype(np.float32))
+        P.prsgd_local_steps(h, 2)
+        P.prsgd_set_iteration(h, 100)
+        P.prsgd_local_steps(h, 2)
+        P.prsgd_local_steps_hetero(h, [1] + [2] * (w.n_workers - 1))
+        P.prsgd_run(h, 4, 2)
+        outs.append(first + (D.read_all(h), P.prsgd_read_loss(h)))
+        P.prsgd_destroy(h)
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+    want = oracle_run(w, inp)
+    assert _bf16_loss_ok(outs[0][1], want["losses"])
+    assert rel_err(outs[0][0], want["x"]) <= 5e-3
+    for i in range(w.n_workers):
+        assert np.array_equal(outs[0][2][i], oracle.sample_rows(w.index_seed, i, w.iterations, w.batch, 256))
+
+
 def test_bf16_fused_backward_kernel_runs_and_falls_back_above_128_rows(P, D):
     # B <= 128: one fused backward kernel per layer; B > 128: the separate products
     for batch, expect in ((48, "gemm_bwd"), (160, "gemm_dw")):
