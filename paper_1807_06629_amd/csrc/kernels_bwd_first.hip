@@ -53,8 +53,10 @@ constexpr size_t first_lds_bytes(int mb) {
   return sizeof(uint16_t) * (br * SD + br * SX + BT * SW) + (hk > gl ? hk : gl) + sizeof(float) * 5 * BT;
 }
 
-// MB: 32-row tiles of the minibatch (B = 32 MB).  NT: non-temporal weight traffic.
-template <int MB, bool NT>
+// MB: 32-row tiles of the minibatch (B = 32 MB).  NT: non-temporal weight traffic.  SHW: also write
+// the bf16 shadow of W_1 (only the stand-alone forward product reads it; the caller may leave it
+// stale while this kernel supplies H_1, and refresh it when that chain breaks).
+template <int MB, bool NT, bool SHW>
 __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   constexpr int BR = 32 * MB;
   constexpr int S = 2;                                // weight tiles in flight
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   const uint16_t* x_g = p.x_next + (size_t)g * p.x_gs;          // X^{t+1}  [B][ldx]
   const uint16_t* d_g = p.d + (size_t)g * p.d_gs;               // D_1      [B][ldd]
   float* w_g = p.params + (size_t)g * p.p_gs + p.w_off;
-  uint16_t* s_g = p.shadow + (size_t)g * p.p_gs + p.w_off;
+  uint16_t* s_g = SHW ? p.shadow + (size_t)g * p.p_gs + p.w_off : nullptr;
   const float* wsrc_g = p.src + (size_t)g * p.src_gs + p.w_off;
   const bool nt_read = NT && p.src_gs != 0;           // a shared source is re-read by every replica
 
@@ -187,10 +189,10 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
                            (uint32_t)f32_to_bf16_rne(w.z) | ((uint32_t)f32_to_bf16_rne(w.w) << 16)};
       if (NT) {
         __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(w_g + off));
-        __builtin_nontemporal_store(hv2, reinterpret_cast<u32x2_t*>(s_g + off));
+        if (SHW) __builtin_nontemporal_store(hv2, reinterpret_cast<u32x2_t*>(s_g + off));
       } else {
         *reinterpret_cast<f32x4_t*>(w_g + off) = w;
-        *reinterpret_cast<u32x2_t*>(s_g + off) = hv2;
+        if (SHW) *reinterpret_cast<u32x2_t*>(s_g + off) = hv2;
       }
       *reinterpret_cast<u32x2_t*>(Wl + row * SW + wcol) = hv2;
     }
@@ -240,26 +242,26 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   }
 }
 
-template <int MB>
+template <int MB, bool SHW>
 hipError_t launch_first_one(const BwdArgs& p, hipStream_t s) {
   constexpr size_t kLds = first_lds_bytes(MB);
   static std::atomic<bool> configured{false};
   if (!configured.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, true>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, true, SHW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, false>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, false, SHW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e != hipSuccess) return e;
     configured.store(true, std::memory_order_release);
   }
   const int bands = p.Nn / BT;
   if (p.streaming)
-    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, true>), dim3((unsigned)(bands * p.n_groups)), dim3(kThreads),
-                       kLds, s, p);
+    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, true, SHW>), dim3((unsigned)(bands * p.n_groups)),
+                       dim3(kThreads), kLds, s, p);
   else
-    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, false>), dim3((unsigned)(bands * p.n_groups)), dim3(kThreads),
-                       kLds, s, p);
+    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, false, SHW>), dim3((unsigned)(bands * p.n_groups)),
+                       dim3(kThreads), kLds, s, p);
   return hipGetLastError();
 }
 
@@ -270,15 +272,16 @@ bool bwd_first_fwd_applies(const BwdArgs& p) {
   if (p.B != 32 && p.B != 64 && p.B != 128) return false;
   if (p.K < 4 * BT || (p.K % (2 * BT)) != 0 || p.Nn < BT || (p.Nn % BT) != 0) return false;
   if (p.vel != nullptr || p.worker_steps != nullptr || p.dx != nullptr) return false;
-  if (p.x_next == nullptr || p.h_next == nullptr || p.shadow == nullptr) return false;
+  if (p.x_next == nullptr || p.h_next == nullptr) return false;   // shadow == nullptr: it is left stale
   return (p.ldw % 4) == 0 && (p.ldh % 8) == 0 && (p.ldx % 8) == 0 && (p.ldd % 8) == 0 && (p.w_off % 4) == 0;
 }
 
 hipError_t launch_bwd_first_fwd(const BwdArgs& p, hipStream_t s) {
   if (!bwd_first_fwd_applies(p) || p.n_groups <= 0) return hipErrorInvalidValue;
-  if (p.B == 32) return launch_first_one<1>(p, s);
-  if (p.B == 64) return launch_first_one<2>(p, s);
-  return launch_first_one<4>(p, s);
+  const bool shw = p.shadow != nullptr;
+  if (p.B == 32) return shw ? launch_first_one<1, true>(p, s) : launch_first_one<1, false>(p, s);
+  if (p.B == 64) return shw ? launch_first_one<2, true>(p, s) : launch_first_one<2, false>(p, s);
+  return shw ? launch_first_one<4, true>(p, s) : launch_first_one<4, false>(p, s);
 }
 
 }  // namespace prsgd

@@ -185,6 +185,8 @@ struct prsgd_ctx {
   int64_t h1_t;
   int h1_batch;
   bool first_fusion;    // let the first layer's backward kernel run the next forward product
+  bool shadow1_stale;   // that kernel skipped the bf16 shadow of W_1 (nothing reads it while the
+                        // chain of ahead-computed activations holds): refresh before any other reader
   float lr;
   char err[256];
   // profiling
@@ -275,6 +277,18 @@ struct Timed {
 
 int materialize(prsgd_ctx* ctx);
 
+// bf16 shadow of W_1 of every replica from its fp32 master (after first-layer kernels that skipped it)
+int refresh_first_shadow(prsgd_ctx* ctx) {
+  const Layout& lo = ctx->lo;
+  const long count = (long)lo.d[0] * lo.ld[1];
+  for (int i = 0; i < ctx->cfg.n_workers; ++i) {
+    const size_t off = (size_t)i * lo.m_pad + lo.w_off[0];
+    LAUNCH(ctx, KK_UPDATE, launch_refresh_shadow(ctx->params + off, ctx->shadow() + off, count, ctx->stream));
+  }
+  ctx->shadow1_stale = false;
+  return PRSGD_OK;
+}
+
 // One local iteration of every (active) MLP worker: gradient observation + eq. (3).
 // fuse_average (interval I = 1, every worker at the node average ybar): step and restart together
 // are one mini-batch SGD step on ybar with the N B samples of all workers (first footnote of
@@ -341,6 +355,10 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   const bool h1_ready = fused_bwd && !from_mean && worker_steps == nullptr && !fuse_average && L >= 2 &&
                         ctx->h1_t == t && ctx->h1_batch == bk;
   ctx->h1_t = -1;
+  if (!h1_ready && ctx->shadow1_stale && !from_mean) {
+    const int rc = refresh_first_shadow(ctx);
+    if (rc != PRSGD_OK) return rc;
+  }
   int logit_parts = 1;
   const long logit_part_stride = (long)N * B * lo.ld[L];
   for (int l = 1; l <= L; ++l) {
@@ -424,7 +442,9 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
       q.x_next = reinterpret_cast<const uint16_t*>(ctx->xb(bk ^ 1)); q.x_gs = (long)B * lo.ld[0]; q.ldx = lo.ld[0];
       q.h_next = ctx->at<uint16_t>(cv.h[1]); q.hn_gs = (long)B * lo.ld[1]; q.ldhn = lo.ld[1];
       if (bwd_first_fwd_applies(q)) {
+        q.shadow = nullptr;                 // replica shadows of W_1 have no reader while H_1 comes from here
         LAUNCH(ctx, KK_BWD_FIRST, launch_bwd_first_fwd(q, s));
+        ctx->shadow1_stale = true;
         ctx->h1_t = t + 1;
         ctx->h1_batch = bk ^ 1;
         continue;
@@ -546,6 +566,7 @@ int check_fused2_abort(prsgd_ctx* ctx) {
 int materialize(prsgd_ctx* ctx) {
   ctx->h1_t = -1;
   if (!ctx->at_mean) return PRSGD_OK;
+  ctx->shadow1_stale = false;               // the broadcast rewrites every shadow
   LAUNCH(ctx, KK_BROADCAST, launch_broadcast(ctx->mean(), ctx->params, ctx->shadow(), ctx->lo.m_pad,
                                              ctx->cfg.n_workers, ctx->stream));
   ctx->at_mean = false;
@@ -683,6 +704,7 @@ int init_common(const prsgd_config* cfg, const float* x0_host, const void* featu
   ctx->h1_t = -1;
   ctx->h1_batch = 0;
   ctx->first_fusion = true;
+  ctx->shadow1_stale = false;
   ctx->lazy_restart = true;
   ctx->at_mean = false;
   ctx->poisoned = false;
@@ -883,6 +905,7 @@ int prsgd_average(prsgd_ctx* ctx) {
   LAUNCH(ctx, KK_AVERAGE,
          launch_average(ctx->params, ctx->shadow(), ctx->lo.m_pad, ctx->cfg.n_workers, ctx->streaming,
                         ctx->stream));
+  ctx->shadow1_stale = false;               // the averaging kernel rewrites every shadow
   return PRSGD_OK;
 }
 
@@ -980,6 +1003,7 @@ int prsgd_write_params(prsgd_ctx* ctx, int32_t worker, const float* in_host, siz
     if (e == hipSuccess)
       e = launch_broadcast(ctx->at<float>(ctx->cv.mean), ctx->params, ctx->shadow(), ctx->lo.m_pad,
                            ctx->cfg.n_workers, ctx->stream);
+    ctx->shadow1_stale = false;
   } else {
     float* dst = ctx->params + (size_t)worker * ctx->lo.m_pad;
     e = hipMemcpyAsync(dst, ctx->host_pad, bytes, hipMemcpyHostToDevice, ctx->stream);
