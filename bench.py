@@ -81,10 +81,11 @@ def algorithmic_work(w, shared_weights=False, first_fused=False):
     bwd_b = sum(n * (di * do * (10 + mom) + b * (di + do) * 2) for di, do in layers) + \
         sum(n * b * di * 2 for di, do in layers[1:])
     out["gemm_bwd"] = {"bytes": bwd_b, "flops": dw_f + dx_f}
-    # first layer, backward + next forward in one pass: master read + write, shadow write, the
-    # minibatches of both iterations, the delta panel, the next activation; both products
+    # first layer, backward + next forward in one pass: master read + write (the shadow is not
+    # written), the minibatches of both iterations, the delta panel, the next activation; both
+    # products
     d0, d1 = layers[0]
-    first_b = n * (d0 * d1 * (10 + mom) + b * (2 * d0 + 2 * d1) * 2)
+    first_b = n * (d0 * d1 * 8 + b * (2 * d0 + 2 * d1) * 2)
     first_f = 4 * n * b * d0 * d1
     out["gemm_bwd_first"] = {"bytes": first_b, "flops": first_f}
     if first_fused:

@@ -7,6 +7,9 @@
 //   backward  D_{l-1} = (D_l W_l^T) * phi'(H_{l-1})        M = B,       N = d_{l-1}, Kc = d_l
 //   weights   dW_l   = H_{l-1}^T D_l ; db_l = colsum(D_l)  M = d_{l-1}, N = d_l,     Kc = B
 //             fused with the local update  W_l <- W_l - gamma dW_l      (Algorithm 1, eq. 3)
+// With I = 1 all workers share the node average: the same products then run with one weight stream
+// (group stride 0) and the weight-gradient product contracts over the stacked minibatches of all
+// workers, M = d_{l-1}, N = d_l, Kc = N B, updating the average in place.
 //
 // A workgroup is 4 wavefronts (8 on the widest tile); each wavefront owns TM x TN accumulator tiles of 32x32
 // (v_mfma_f32_32x32x16_bf16 or v_mfma_f32_32x32x2_f32).  Operand tiles are staged through LDS in
