@@ -361,13 +361,22 @@ def main() -> int:
     work = algorithmic_work(w, shared_weights=one_pass, first_fused=first_fused)
     prof_key = w.name + ("_I1" if one_pass else "")      # counter readings are kept per launch pattern
     kernels = {}
+    # the work table is per iteration; kernels launched once per layer are priced per launch (they do
+    # not run in every iteration: the pass that closes an epoch replaces the per-replica backward
+    # kernels by backward-data products and the stacked weight-gradient product)
+    n_layers = len(w.dims) - 1
+    per_iteration_launches = {"gemm_fwd": n_layers - (1 if first_fused else 0),
+                              "gemm_bwd": n_layers - (1 if first_fused else 0),
+                              "gemm_dx": n_layers - 1, "gemm_dw": n_layers, "step_mean": n_layers}
     for s in stats:
         per_iter = work.get(s["name"], {"bytes": 0, "flops": 0})
         calls = prof_steps if s["name"] not in ("average", "restart_mean") else max(1, prof_steps // w.interval)
         if s["name"] in ("lsq_steps", "mlp2_epoch"):
             calls = prof_steps                        # one launch covers several iterations
-        if s["name"] == "gather":
-            calls = s["launches"]                     # only when no draw made ahead is waiting
+        if s["name"] in ("gather", "gemm_bwd_first", "softmax_xent", "sgd_update"):
+            calls = s["launches"]                     # one launch per iteration in which they run
+        if s["name"] in per_iteration_launches and w.model == "mlp":
+            calls = s["launches"] / max(1, per_iteration_launches[s["name"]])
         tot_bytes, tot_flops = per_iter["bytes"] * calls, per_iter["flops"] * calls
         sec = s["total_ms"] * 1e-3
         kernels[s["name"]] = {

@@ -157,8 +157,8 @@ int prsgd_average(prsgd_ctx* ctx);
 /*
  * on = 0: every prsgd_average overwrites all replicas at once (one read and one write of the
  * whole replica set: the stand-alone averaging kernel).  on = 1 (default): deferred broadcast.
- * Results are identical either way, except that prsgd_run with interval = 1 takes its one-pass
- * form (see there; equal up to fp32 rounding) only with the deferred broadcast.
+ * Results are identical either way, except that prsgd_run takes an epoch's last iteration and the
+ * restart as one pass (see there; equal up to fp32 rounding) only with the deferred broadcast.
  */
 int prsgd_set_lazy_restart(prsgd_ctx* ctx, int32_t on);
 
@@ -166,14 +166,16 @@ int prsgd_set_lazy_restart(prsgd_ctx* ctx, int32_t on);
  * Algorithm 1 for `iterations` iterations from the current counter t: local steps, and an
  * average after every iteration whose number is a multiple of `interval` (so a run whose
  * length is not a multiple of the interval ends un-averaged).
- * interval = 1 (parallel mini-batch SGD, first footnote of Section 1): for MLPs with bf16 operands,
- * plain SGD, the fused update and the deferred broadcast (the defaults), every iteration that
- * starts with all workers at the node average ybar -- all but the first of a run -- is taken as
- *   ybar <- ybar - (gamma / N) sum_i G_i(ybar),
- * the weight gradients of all N minibatches contracted as one product of N B rows: equal to
- * (1/N) sum_i (ybar - gamma G_i) of eq. (2)-(3) up to fp32 rounding (one rounding per parameter
- * instead of N + 1; gamma / N is rounded to fp32).  The replicas are not rewritten in between;
- * every worker's point reads as ybar.
+ * For MLPs with bf16 operands, plain SGD, the fused update and the deferred broadcast (the defaults)
+ * the iteration that completes an epoch and the restart after it are taken as one pass,
+ *   ybar' = (1/N) sum_i (x_i - gamma G_i(x_i)) = ybar - (gamma / N) sum_i G_i(x_i),  ybar = (1/N) sum_i x_i:
+ * ybar is averaged from the points as they are, the weight gradients of all N minibatches are
+ * contracted as one product of N B rows and applied to it; the replicas are not rewritten (every
+ * worker's point reads as ybar').  Equal to eq. (2)-(3) taken one after the other up to fp32
+ * rounding (gamma / N is rounded to fp32; fewer roundings per parameter).  With interval = 1 every
+ * iteration after the first starts at ybar and is exactly one mini-batch SGD step with the N B
+ * samples of all workers (first footnote of Section 1).  prsgd_local_steps followed by
+ * prsgd_average always runs the two kernels separately.
  */
 int prsgd_run(prsgd_ctx* ctx, int64_t iterations, int32_t interval);
 

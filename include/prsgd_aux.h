@@ -37,6 +37,13 @@ int prsgd_set_epoch_wait_limit(prsgd_ctx* ctx, uint32_t polls);
  */
 int prsgd_set_first_layer_fusion(prsgd_ctx* ctx, int32_t on);
 
+/*
+ * on = 1 (default): prsgd_run takes the iteration that completes an epoch and the restart after it
+ * as one pass (see prsgd_run in prsgd.h).  on = 0: local iteration, then the restart kernel; equal
+ * up to fp32 rounding.  Tests compare the two.
+ */
+int prsgd_set_restart_fusion(prsgd_ctx* ctx, int32_t on);
+
 #ifdef __cplusplus
 }
 #endif

@@ -184,6 +184,7 @@ struct prsgd_ctx {
   // iteration h1_t on batch set h1_batch while the replicas are untouched (-1: none)
   int64_t h1_t;
   int h1_batch;
+  bool restart_fusion;  // prsgd_run: take an epoch's last iteration and the restart as one pass
   bool first_fusion;    // let the first layer's backward kernel run the next forward product
   bool shadow1_stale;   // that kernel skipped the bf16 shadow of W_1 (nothing reads it while the
                         // chain of ahead-computed activations holds): refresh before any other reader
@@ -290,11 +291,12 @@ int refresh_first_shadow(prsgd_ctx* ctx) {
 }
 
 // One local iteration of every (active) MLP worker: gradient observation + eq. (3).
-// fuse_average (interval I = 1, every worker at the node average ybar): step and restart together
-// are one mini-batch SGD step on ybar with the N B samples of all workers (first footnote of
-// Section 1): (1/N) sum_i (ybar - gamma G_i) = ybar - (gamma / N) sum_i G_i.  The backward pass
-// contracts over the stacked minibatches and writes only the new ybar; the replicas stay stale
-// and the context stays "at the mean".
+// fuse_average: this iteration is followed by a restart, and both are taken together,
+//   (1/N) sum_i (x_i - gamma G_i) = ybar - (gamma / N) sum_i G_i,   ybar = (1/N) sum_i x_i   (eq. 2-3).
+// The backward pass contracts over the stacked minibatches of all workers and writes only the new
+// ybar; the replicas are not rewritten and the context ends "at the mean".  With every worker
+// already at ybar (I = 1) it is one mini-batch SGD step with the N B samples of all workers (first
+// footnote of Section 1).
 int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool fuse_average = false) {
   const prsgd_config& c = ctx->cfg;
   const Layout& lo = ctx->lo;
@@ -352,7 +354,7 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
 
   // forward.  H_1 may already be there: the previous iteration's first-layer backward kernel computes
   // it from the weights it writes, for this iteration's minibatch
-  const bool h1_ready = fused_bwd && !from_mean && worker_steps == nullptr && !fuse_average && L >= 2 &&
+  const bool h1_ready = fused_bwd && !from_mean && worker_steps == nullptr && L >= 2 &&
                         ctx->h1_t == t && ctx->h1_batch == bk;
   ctx->h1_t = -1;
   if (!h1_ready && ctx->shadow1_stale && !from_mean) {
@@ -393,13 +395,21 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   if (prefetch) ctx->batch_t[bk ^ 1] = t + 1;
 
   if (fuse_average) {
-    // eq. (3) from the common point and eq. (2) in one pass over ybar, layer by layer from the
-    // top: D_{l-1} needs the old ybar_l (its bf16 image), so it runs before layer l's pass
+    // The workers' points differ (the last iteration of an epoch with I >= 2, or the first
+    // iteration of a run): ybar is first taken from the points as they are (the restart kernel),
+    // then moved by the averaged gradient; the points themselves are not rewritten.
+    if (!from_mean)
+      LAUNCH(ctx, KK_RESTART_MEAN,
+             launch_mean(ctx->params, ctx->mean(), ctx->mean_shadow(), lo.m_pad, N, ctx->streaming, s));
+    // eq. (3) and eq. (2) in one pass over ybar, layer by layer from the top: D_{l-1} needs the
+    // weights the forward pass used (the bf16 image of ybar, or of every worker's own point), and
+    // when that is ybar it runs before layer l's pass changes it
     for (int l = L; l >= 1; --l) {
       if (l > 1) {
         GemmArgs p = base;
         p.a = ctx->at<void>(cv.delta[l]); p.a_gs = (long)B * lo.ld[l]; p.lda = lo.ld[l];
-        p.b = (const void*)(ctx->mean_shadow() + lo.w_off[l - 1]); p.b_gs = 0; p.ldb = lo.ld[l];
+        p.b = (const void*)((from_mean ? ctx->mean_shadow() : ctx->shadow()) + lo.w_off[l - 1]);
+        p.b_gs = from_mean ? 0 : lo.m_pad; p.ldb = lo.ld[l];
         p.M = B; p.N = lo.d[l - 1]; p.Kc = lo.d[l];
         p.epi = EPI_DX;
         p.out = ctx->at<void>(cv.delta[l - 1]); p.out_gs = (long)B * lo.ld[l - 1];
@@ -419,7 +429,8 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
       p.w_off = lo.w_off[l - 1]; p.b_off = lo.b_off[l - 1]; p.ldw = lo.ld[l];
       LAUNCH(ctx, KK_STEP_MEAN, launch_gemm_dw_stacked(p, s));
     }
-    return PRSGD_OK;                 // still at the (new) mean; the replicas were not touched
+    ctx->at_mean = true;             // every worker's point is the new ybar; the replicas are stale
+    return PRSGD_OK;
   }
 
   // backward.  bf16 operands with the fused update: one kernel per layer does the weight
@@ -704,6 +715,7 @@ int init_common(const prsgd_config* cfg, const float* x0_host, const void* featu
   ctx->h1_t = -1;
   ctx->h1_batch = 0;
   ctx->first_fusion = true;
+  ctx->restart_fusion = true;
   ctx->shadow1_stale = false;
   ctx->lazy_restart = true;
   ctx->at_mean = false;
@@ -923,18 +935,23 @@ int prsgd_run(prsgd_ctx* ctx, int64_t iterations, int32_t interval) {
   if (ctx == nullptr) return PRSGD_EINVAL;
   if (iterations < 0 || interval < 1) return set_err(ctx, PRSGD_EINVAL, "iterations >= 0, interval >= 1");
   int64_t left = iterations;
-  // I = 1 with plain SGD on bf16 operands: once the workers sit at the node average (after the
-  // first restart) every further iteration is one pass over ybar -- step and restart together
-  const bool can_fuse = interval == 1 && ctx->cfg.model == PRSGD_MLP && ctx->bf16 && ctx->cfg.fused_update &&
+  // Plain SGD on bf16 operands with the deferred broadcast: the iteration that completes an epoch
+  // and the restart after it are one pass that writes only ybar (with I = 1: every iteration)
+  const bool can_fuse = ctx->cfg.model == PRSGD_MLP && ctx->bf16 && ctx->cfg.fused_update &&
                         ctx->cfg.momentum == 0.0f && ctx->lazy_restart && !ctx->use_fused2 &&
-                        bwd_fused_supported(ctx->cfg.batch);
+                        ctx->restart_fusion && bwd_fused_supported(ctx->cfg.batch);
   while (left > 0) {
-    if (can_fuse && ctx->at_mean) {
+    if (can_fuse && interval - (ctx->t % interval) <= left) {
+      const int64_t k_epoch = interval - (ctx->t % interval);
+      if (k_epoch > 1) {
+        const int rc = prsgd_local_steps(ctx, (int32_t)(k_epoch - 1));
+        if (rc != PRSGD_OK) return rc;
+      }
       if (check_poisoned(ctx) != PRSGD_OK) return PRSGD_ESTATE;
       const int rc = mlp_step(ctx, ctx->t + 1, nullptr, 0, true);
       if (rc != PRSGD_OK) return rc;
       ctx->t += 1;
-      left -= 1;
+      left -= k_epoch;
       continue;
     }
     int64_t k = interval - (ctx->t % interval);      // steps until the next multiple of I
@@ -1114,6 +1131,12 @@ int prsgd_status(prsgd_ctx* ctx) {
   if (arc != PRSGD_OK) return arc;
   const hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e, "prsgd_status");
+  return PRSGD_OK;
+}
+
+int prsgd_set_restart_fusion(prsgd_ctx* ctx, int32_t on) {
+  if (ctx == nullptr) return PRSGD_EINVAL;
+  ctx->restart_fusion = on != 0;
   return PRSGD_OK;
 }
 

@@ -86,6 +86,7 @@ def _load() -> ctypes.CDLL:
         "prsgd_status": (ctypes.c_int, [vp]),
         "prsgd_set_epoch_wait_limit": (ctypes.c_int, [vp, ctypes.c_uint32]),
         "prsgd_set_first_layer_fusion": (ctypes.c_int, [vp, i32]),
+        "prsgd_set_restart_fusion": (ctypes.c_int, [vp, i32]),
         "prsgd_set_lr": (ctypes.c_int, [vp, ctypes.c_float]),
         "prsgd_set_iteration": (ctypes.c_int, [vp, i64]),
         "prsgd_iteration": (i64, [vp]),
@@ -325,6 +326,10 @@ def prsgd_status(h: Handle) -> None:
 
 def prsgd_set_epoch_wait_limit(h: Handle, polls: int) -> None:
     _check(_lib.prsgd_set_epoch_wait_limit(h.ctx, int(polls)), h.ctx)
+
+
+def prsgd_set_restart_fusion(h: Handle, on: bool) -> None:
+    _check(_lib.prsgd_set_restart_fusion(h.ctx, 1 if on else 0), h.ctx)
 
 
 def prsgd_set_first_layer_fusion(h: Handle, on: bool) -> None:

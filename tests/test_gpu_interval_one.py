@@ -1,6 +1,8 @@
-"""GPU parity of the interval-1 path that takes the local step and the restart in one pass over the
-node average: Algorithm 1 with I = 1 is parallel mini-batch SGD (first footnote of Section 1), one
-step on the common point with the gradient averaged over the N B samples of all workers."""
+"""GPU parity of the pass that takes an epoch's last local iteration and the restart together,
+    (1/N) sum_i (x_i - gamma G_i) = ybar - (gamma / N) sum_i G_i,   ybar = (1/N) sum_i x_i   (eq. 2-3).
+With I = 1 every worker already sits at ybar and the pass is one step of parallel mini-batch SGD on
+the common point with the gradient averaged over the N B samples of all workers (first footnote of
+Section 1)."""
 import numpy as np
 import pytest
 import torch
@@ -133,3 +135,32 @@ def test_single_pass_with_time_varying_rates(P, D):
     xbar = oracle.node_average(want["x"])               # the GPU run ends on a restart
     assert rel_err(P.prsgd_read_params(h, -1)[None], xbar[None]) <= 5e-3
     P.prsgd_destroy(h)
+
+
+@pytest.mark.parametrize("shape", SHAPES[:4] + [dict(dims=(256, 128, 64, 10), batch=32, n_workers=4)])
+@pytest.mark.parametrize("interval", [2, 3])
+def test_last_iteration_of_an_epoch_taken_with_the_restart(P, D, shape, interval):
+    """I >= 2: the pass against the separate kernels (local iteration, then the restart kernel) after
+    one epoch: fp32 rounding apart; both against the oracle over several epochs; a run that ends inside
+    an epoch ends with distinct replicas."""
+    w = small_mlp(activation="relu", gemm_dtype="bf16", interval=interval, iterations=2 * interval + 1,
+                  rows_per_worker=256, **shape)
+    inp = inputs_for(w)
+    outs = []
+    for fused in (True, False):
+        h = D.open_workload(w, inp, device="cuda:0")
+        P.prsgd_set_restart_fusion(h, fused)
+        names = _names(P, h, interval, interval)             # exactly one epoch
+        assert ("step_mean" in names) == fused and "restart_mean" in names, names
+        one_epoch = P.prsgd_read_params(h, -1)
+        for i in (0, w.n_workers - 1):                       # every worker reads as the average
+            assert np.array_equal(P.prsgd_read_params(h, i), one_epoch)
+        P.prsgd_run(h, w.iterations - interval, interval)    # one more epoch and one iteration into the next
+        outs.append((one_epoch, D.read_all(h), P.prsgd_read_loss(h)))
+        P.prsgd_destroy(h)
+    assert rel_err(outs[0][0][None], outs[1][0][None]) <= 1e-5
+    want = oracle_run(w, inp)
+    for _, xs, losses in outs:
+        assert not np.array_equal(xs[0], xs[1])              # the run ended inside an epoch
+        assert rel_err(xs, want["x"]) <= 5e-3
+        assert np.all(np.abs(losses - want["losses"]) <= BF16_LOSS_TOL * np.abs(want["losses"]) + LOSS_QUANTUM)
