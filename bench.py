@@ -42,6 +42,7 @@ KERNEL_SYMBOL = {
     "lsq_steps": "lsq_steps_staged_kernel (lsq_steps_kernel for shapes it does not take)",
     "mlp2_epoch": "mlp2_epoch_kernel",
     "gemm_bwd_first": "bwd_first_fwd_kernel (layer 1: backward step + next forward product)",
+    "refresh_shadow": "refresh_shadow_kernel (bf16 image of W_1 when the first-layer chain breaks)",
     "step_mean": "grouped_gemm_kernel<.., OP_TRANS, OP_TRANS, true> (the minibatches of all workers "
                  "stacked into one contraction)",
 }
@@ -279,7 +280,7 @@ def main() -> int:
     ap.add_argument("--copy-mib", type=int, default=1024)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the N workers are simulated on it); "
+        print("bench.py: the library runs on one GPU only (the N workers are simulated on it); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         return 2
 

@@ -19,7 +19,7 @@ namespace prsgd {
 const char* kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {"gather",  "gemm_fwd", "softmax_xent", "gemm_dx",   "gemm_dw",
                                         "sgd_update", "average", "mean",       "broadcast", "lsq_steps",
-                                        "mlp2_epoch", "gemm_bwd", "restart_mean", "step_mean", "gemm_bwd_first"};
+                                        "mlp2_epoch", "gemm_bwd", "restart_mean", "step_mean", "gemm_bwd_first", "refresh_shadow"};
   return (kind >= 0 && kind < KK_COUNT) ? names[kind] : "?";
 }
 }  // namespace prsgd
@@ -284,7 +284,7 @@ int refresh_first_shadow(prsgd_ctx* ctx) {
   const long count = (long)lo.d[0] * lo.ld[1];
   for (int i = 0; i < ctx->cfg.n_workers; ++i) {
     const size_t off = (size_t)i * lo.m_pad + lo.w_off[0];
-    LAUNCH(ctx, KK_UPDATE, launch_refresh_shadow(ctx->params + off, ctx->shadow() + off, count, ctx->stream));
+    LAUNCH(ctx, KK_REFRESH, launch_refresh_shadow(ctx->params + off, ctx->shadow() + off, count, ctx->stream));
   }
   ctx->shadow1_stale = false;
   return PRSGD_OK;

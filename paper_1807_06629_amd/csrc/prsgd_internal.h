@@ -69,7 +69,7 @@ constexpr int kMaxLogitSplits = 4;
 
 enum KernelKind {
   KK_GATHER = 0, KK_FWD, KK_LOSS, KK_DX, KK_DW, KK_UPDATE, KK_AVERAGE, KK_MEAN, KK_BROADCAST,
-  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_STEP_MEAN, KK_BWD_FIRST, KK_COUNT
+  KK_LSQ, KK_FUSED2, KK_BWD, KK_RESTART_MEAN, KK_STEP_MEAN, KK_BWD_FIRST, KK_REFRESH, KK_COUNT
 };
 
 // Fused backward step of one layer with bf16 operands (kernels_bwd.hip): weight gradient, local

@@ -71,3 +71,34 @@ def test_traffic_table_is_keyed_by_the_kernel_sources():
     digest = bench.kernel_source_digest()
     assert len(digest) == 64
     assert bench.measured_traffic("no-such-workload", "gemm_bwd") is None
+
+
+def test_first_layer_pass_moves_eight_bytes_per_weight_element_and_takes_its_layer_out_of_the_others():
+    w = get_workload("c5")
+    n, b = w.n_workers, w.batch
+    d0, d1 = w.dims[0], w.dims[1]
+    plain, fused = bench.algorithmic_work(w), bench.algorithmic_work(w, first_fused=True)
+    first = fused["gemm_bwd_first"]
+    # master read + write; minibatches of both iterations, delta panel, next activation (bf16)
+    assert first["bytes"] == n * (8 * d0 * d1 + 2 * b * (2 * d0 + 2 * d1))
+    assert first["flops"] == 2 * (2 * n * b * d0 * d1)                 # weight gradient + next forward
+    # the other labels lose exactly layer 1
+    assert plain["gemm_fwd"]["flops"] - fused["gemm_fwd"]["flops"] == 2 * n * b * d0 * d1
+    assert plain["gemm_bwd"]["flops"] - fused["gemm_bwd"]["flops"] == 2 * n * b * d0 * d1
+    assert plain["gemm_bwd"]["bytes"] - fused["gemm_bwd"]["bytes"] == n * (10 * d0 * d1 + 2 * b * (d0 + d1))
+    # per weight element and iteration: 12 B for layers 2..L, 8 B for layer 1 (weights only)
+    pw_rest = _pw(w.dims) - d0 * d1
+    weights_only = 8 * n * d0 * d1 + 12 * n * pw_rest
+    assert abs(weights_only / 1e9 - 4.688) < 0.005
+
+
+def test_stacked_product_of_the_epoch_closing_pass():
+    w = get_workload("c5")
+    n, b = w.n_workers, w.batch
+    work = bench.algorithmic_work(w, shared_weights=True)
+    panels = sum(n * b * (di + do) * 2 for di, do in zip(w.dims[:-1], w.dims[1:]))
+    # the node average read and written once, its bf16 image written once, every panel read once
+    assert work["step_mean"]["bytes"] == 8 * _m(w.dims) + 2 * _pw(w.dims) + panels
+    assert work["step_mean"]["flops"] == 2 * n * b * _pw(w.dims)
+    # shared weights: the forward products read one weight matrix per layer, not one per worker
+    assert bench.algorithmic_work(w)["gemm_fwd"]["bytes"] - work["gemm_fwd"]["bytes"] == 2 * (n - 1) * _pw(w.dims)

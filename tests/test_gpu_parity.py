@@ -1,6 +1,6 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on identical seeded inputs.
 
-Gates (stated by the task this build serves, norm = max over replicas of
+Gates (norm = max over replicas of
 ||got - want||_inf / ||want||_inf):
     minibatch indices              bit-exact
     fp32 parameters, one step      <= 1e-5
