@@ -567,6 +567,26 @@ def test_deferred_broadcast_gives_the_same_run_as_the_averaging_kernel(P, D, kin
         assert rel_err(outs[0][0], want["x"]) <= 1e-4
 
 
+def test_deferred_broadcast_is_bit_identical_when_stepped_by_hand_with_bf16_operands(P, D):
+    # prsgd_local_steps + prsgd_average never take the one-pass form: with or without the broadcast
+    # deferred the same kernels update the replicas, and the results agree bit for bit
+    w = small_mlp(dims=(256, 128, 64, 10), batch=32, n_workers=4, gemm_dtype="bf16", activation="relu",
+                  rows_per_worker=128)
+    inp = inputs_for(w)
+    outs = []
+    for lazy in (True, False):
+        h = _open(D, w, inp)
+        P.prsgd_set_lazy_restart(h, lazy)
+        for k in (2, 1, 3):
+            P.prsgd_local_steps(h, k)
+            P.prsgd_average(h)
+        P.prsgd_local_steps(h, 1)
+        outs.append((D.read_all(h), P.prsgd_read_params(h, -1), P.prsgd_read_loss(h)))
+        P.prsgd_destroy(h)
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+
+
 def test_state_right_after_a_deferred_restart(P, D):
     w = small_mlp(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="relu",
                   rows_per_worker=128)
