@@ -86,7 +86,7 @@ def algorithmic_work(w, shared_weights=False, first_fused=False):
     # written), the minibatches of both iterations, the delta panel, the next activation; both
     # products
     d0, d1 = layers[0]
-    first_b = n * (d0 * d1 * 8 + b * (2 * d0 + 2 * d1) * 2)
+    first_b = n * (d0 * d1 * (8 + mom) + b * (2 * d0 + 2 * d1) * 2)
     first_f = 4 * n * b * d0 * d1
     out["gemm_bwd_first"] = {"bytes": first_b, "flops": first_f}
     if first_fused:

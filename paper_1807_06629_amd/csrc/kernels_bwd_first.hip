@@ -55,8 +55,10 @@ constexpr size_t first_lds_bytes(int mb) {
 
 // MB: 32-row tiles of the minibatch (B = 32 MB).  NT: non-temporal weight traffic.  SHW: also write
 // the bf16 shadow of W_1 (only the stand-alone forward product reads it; the caller may leave it
-// stale while this kernel supplies H_1, and refresh it when that chain breaks).
-template <int MB, bool NT, bool SHW>
+// stale while this kernel supplies H_1, and refresh it when that chain breaks).  MOM: momentum form
+// of the local update, v <- mu v + G, x <- x - gamma v, with the velocity tile streamed beside the
+// weights.
+template <int MB, bool NT, bool SHW, bool MOM>
 __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   constexpr int BR = 32 * MB;
   constexpr int S = 2;                                // weight tiles in flight
@@ -95,6 +97,7 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   float* w_g = p.params + (size_t)g * p.p_gs + p.w_off;
   uint16_t* s_g = SHW ? p.shadow + (size_t)g * p.p_gs + p.w_off : nullptr;
   const float* wsrc_g = p.src + (size_t)g * p.src_gs + p.w_off;
+  float* v_g = MOM ? p.vel + (size_t)g * p.p_gs + p.w_off : nullptr;
   const bool nt_read = NT && p.src_gs != 0;           // a shared source is re-read by every replica
 
   const int prow = tid >> 3, pcol = (tid & 7) * 8;              // panels: row q*32 + prow
@@ -117,16 +120,27 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
       reg[q] = nt_read ? __builtin_nontemporal_load(src) : *src;
     }
   };
+  auto fetch_v = [&](f32x4_t (&reg)[4], int k0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4_t* src =
+          reinterpret_cast<const f32x4_t*>(v_g + (size_t)(k0 + q * 16 + wrow) * p.ldw + n0 + wcol);
+      reg[q] = NT ? __builtin_nontemporal_load(src) : *src;
+    }
+  };
 
   const int n_t = p.K / BT;                           // steps of the walk down the rows
   u32x4_t hr[MB], xr[MB];
   f32x4_t wr[S][4];
+  f32x4_t vr[MOM ? S : 1][4];
   fetch_panel(hr, d_g, p.ldd, n0);                    // the D_1 band first (through hr)
   fetch_w(wr[0], 0);
+  if (MOM) fetch_v(vr[0], 0);
   stash_panel(Dn, SD, hr);
   fetch_panel(hr, h_g, p.ldh, 0);
   fetch_panel(xr, x_g, p.ldx, 0);
   fetch_w(wr[1], BT);
+  if (MOM) fetch_v(vr[1], BT);
   __syncthreads();
 
   // b_1 <- b_1 - gamma db_1: four quarter sums over the minibatch rows, added in order
@@ -138,8 +152,13 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   }
   __syncthreads();
   if (tid < BT) {
-    const float cs = ((Bs[tid] + Bs[BT + tid]) + Bs[2 * BT + tid]) + Bs[3 * BT + tid];
+    float cs = ((Bs[tid] + Bs[BT + tid]) + Bs[2 * BT + tid]) + Bs[3 * BT + tid];
     const size_t bo = p.b_off + (size_t)n0 + tid;
+    if (MOM) {
+      float* vb = p.vel + (size_t)g * p.p_gs + bo;
+      cs = fmaf(p.mu, *vb, cs);
+      *vb = cs;
+    }
     const float b_new = fmaf(-p.lr, cs, p.src[(size_t)g * p.src_gs + bo]);
     p.params[(size_t)g * p.p_gs + bo] = b_new;
     Bn[tid] = b_new;
@@ -153,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
 
   // One step of the walk: rows k0 .. k0 + 63 of the band.  PF: fetch the weight tile S steps ahead.
   // NEXT: fetch the next minibatch tiles.  (Both flags are literal at every call site.)
-  auto tile_step = [&](int it, f32x4_t (&wr)[4], const bool PF, const bool NEXT) __attribute__((always_inline)) {
+  auto tile_step = [&](int it, f32x4_t (&wr)[4], f32x4_t (&vr)[4], const bool PF, const bool NEXT) __attribute__((always_inline)) {
     const int k0 = it * BT;
     stash_panel(Hk, SH, hr);
     stash_panel(Xk, SX, xr);
@@ -178,8 +197,16 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int row = q * 16 + wrow;
-      const f32x4_t gr = *reinterpret_cast<const f32x4_t*>(Gl + row * SG + wcol);
+      f32x4_t gr = *reinterpret_cast<const f32x4_t*>(Gl + row * SG + wcol);
       const size_t off = (size_t)(k0 + row) * p.ldw + n0 + wcol;
+      if (MOM) {
+        gr.x = fmaf(p.mu, vr[q].x, gr.x);
+        gr.y = fmaf(p.mu, vr[q].y, gr.y);
+        gr.z = fmaf(p.mu, vr[q].z, gr.z);
+        gr.w = fmaf(p.mu, vr[q].w, gr.w);
+        if (NT) __builtin_nontemporal_store(gr, reinterpret_cast<f32x4_t*>(v_g + off));
+        else *reinterpret_cast<f32x4_t*>(v_g + off) = gr;
+      }
       f32x4_t w = wr[q];
       w.x = fmaf(-p.lr, gr.x, w.x);
       w.y = fmaf(-p.lr, gr.y, w.y);
@@ -209,20 +236,23 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
                                acc_z[t]);
       }
     }
-    if (PF) fetch_w(wr, k0 + S * BT);
+    if (PF) {
+      fetch_w(wr, k0 + S * BT);
+      if (MOM) fetch_v(vr, k0 + S * BT);
+    }
     __syncthreads();                                  // the tiles in LDS are rewritten by the next step
   };
 
   int it = 0;
 #pragma unroll
-  for (int st = 0; st < S; ++st) tile_step(st, wr[st], true, true);
+  for (int st = 0; st < S; ++st) tile_step(st, wr[st], vr[MOM ? st : 0], true, true);
   for (it = S; it < n_t - S; it += S) {
 #pragma unroll
-    for (int st = 0; st < S; ++st) tile_step(it + st, wr[st], true, true);
+    for (int st = 0; st < S; ++st) tile_step(it + st, wr[st], vr[MOM ? st : 0], true, true);
   }
 #pragma unroll
   for (int st = 0; st < S; ++st)                      // the last S tiles: nothing left to prefetch
-    tile_step(it + st, wr[st], false, st + 1 < S);
+    tile_step(it + st, wr[st], vr[MOM ? st : 0], false, st + 1 < S);
 
   // ---- H_1^{t+1} = phi(Z + b_1) for this band ------------------------------------------------------
   uint16_t* hn_g = p.h_next + (size_t)g * p.hn_gs;
@@ -242,46 +272,52 @@ __global__ __launch_bounds__(kThreads) void bwd_first_fwd_kernel(BwdArgs p) {
   }
 }
 
-template <int MB, bool SHW>
+template <int MB, bool SHW, bool MOM>
 hipError_t launch_first_one(const BwdArgs& p, hipStream_t s) {
   constexpr size_t kLds = first_lds_bytes(MB);
   static std::atomic<bool> configured{false};
   if (!configured.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, true, SHW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, true, SHW, MOM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, false, SHW>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_first_fwd_kernel<MB, false, SHW, MOM>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e != hipSuccess) return e;
     configured.store(true, std::memory_order_release);
   }
   const int bands = p.Nn / BT;
   if (p.streaming)
-    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, true, SHW>), dim3((unsigned)(bands * p.n_groups)),
+    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, true, SHW, MOM>), dim3((unsigned)(bands * p.n_groups)),
                        dim3(kThreads), kLds, s, p);
   else
-    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, false, SHW>), dim3((unsigned)(bands * p.n_groups)),
+    hipLaunchKernelGGL((bwd_first_fwd_kernel<MB, false, SHW, MOM>), dim3((unsigned)(bands * p.n_groups)),
                        dim3(kThreads), kLds, s, p);
   return hipGetLastError();
 }
 
+template <int MB>
+hipError_t launch_first_mb(const BwdArgs& p, hipStream_t s) {
+  const bool shw = p.shadow != nullptr, mom = p.vel != nullptr;
+  if (mom) return shw ? launch_first_one<MB, true, true>(p, s) : launch_first_one<MB, false, true>(p, s);
+  return shw ? launch_first_one<MB, true, false>(p, s) : launch_first_one<MB, false, false>(p, s);
+}
+
 }  // namespace
 
-// Whole tiles, plain SGD, every worker active, and the buffers of the next iteration given.
+// Whole tiles, every worker active, and the buffers of the next iteration given.
 bool bwd_first_fwd_applies(const BwdArgs& p) {
   if (p.B != 32 && p.B != 64 && p.B != 128) return false;
   if (p.K < 4 * BT || (p.K % (2 * BT)) != 0 || p.Nn < BT || (p.Nn % BT) != 0) return false;
-  if (p.vel != nullptr || p.worker_steps != nullptr || p.dx != nullptr) return false;
+  if (p.worker_steps != nullptr || p.dx != nullptr) return false;
   if (p.x_next == nullptr || p.h_next == nullptr) return false;   // shadow == nullptr: it is left stale
   return (p.ldw % 4) == 0 && (p.ldh % 8) == 0 && (p.ldx % 8) == 0 && (p.ldd % 8) == 0 && (p.w_off % 4) == 0;
 }
 
 hipError_t launch_bwd_first_fwd(const BwdArgs& p, hipStream_t s) {
   if (!bwd_first_fwd_applies(p) || p.n_groups <= 0) return hipErrorInvalidValue;
-  const bool shw = p.shadow != nullptr;
-  if (p.B == 32) return shw ? launch_first_one<1, true>(p, s) : launch_first_one<1, false>(p, s);
-  if (p.B == 64) return shw ? launch_first_one<2, true>(p, s) : launch_first_one<2, false>(p, s);
-  return shw ? launch_first_one<4, true>(p, s) : launch_first_one<4, false>(p, s);
+  if (p.B == 32) return launch_first_mb<1>(p, s);
+  if (p.B == 64) return launch_first_mb<2>(p, s);
+  return launch_first_mb<4>(p, s);
 }
 
 }  // namespace prsgd
