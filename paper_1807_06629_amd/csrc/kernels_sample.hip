@@ -157,6 +157,75 @@ __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
   if (lane == 0) row_loss[r] = (mx + logf(se)) - z_label;
 }
 
+// The same head for wide class counts (257 .. 1024): one workgroup per minibatch row, at most four
+// classes per thread, so that a row's loads are spread over four wavefronts instead of queueing in
+// one (1000 classes, four partial sums per logit: 20 loads per lane instead of 80).
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void softmax_xent_row_kernel(
+    const float* __restrict__ logits, int n_parts, long part_stride, const float* __restrict__ bias,
+    long bias_gs, const int32_t* __restrict__ yb, void* __restrict__ delta,
+    float* __restrict__ row_loss, int batch, int n_classes, int ldc,
+    const int* __restrict__ worker_steps, int step, int head_blocks, GatherArgs next) {
+  const int g = blockIdx.y;
+  if ((int)blockIdx.x >= head_blocks) {                 // the minibatch draw of the next iteration
+    gather_row<BF16>(next, (int)blockIdx.x - head_blocks, g);
+    return;
+  }
+  if (worker_steps != nullptr && step >= worker_steps[g]) return;
+  __shared__ float red[3][kThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t r = (size_t)g * batch + blockIdx.x;
+  const float inv_b = 1.0f / (float)batch;
+  const float* bias_g = bias != nullptr ? bias + (size_t)g * bias_gs : nullptr;
+  const int label = yb[r];
+  constexpr int ZT = 4;                                 // classes per thread
+  float z[ZT];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < ZT; ++q) {
+    const int c = tid + kThreads * q;
+    float v = -INFINITY;
+    if (c < n_classes) {                                // bias plus the partial sums in split order
+      v = bias_g != nullptr ? bias_g[c] : 0.0f;
+      for (int s = 0; s < n_parts; ++s) v += logits[(size_t)s * part_stride + r * ldc + c];
+    }
+    z[q] = v;
+    mx = fmaxf(mx, v);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (lane == 0) red[0][wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+  float se = 0.0f, zl = 0.0f;                           // the label's logit lives in one thread
+#pragma unroll
+  for (int q = 0; q < ZT; ++q) {
+    const int c = tid + kThreads * q;
+    if (c == label && c < n_classes) zl = z[q];
+    z[q] = c < n_classes ? expf(z[q] - mx) : 0.0f;
+    se += z[q];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    se += __shfl_xor(se, o);
+    zl += __shfl_xor(zl, o);
+  }
+  if (lane == 0) { red[1][wave] = se; red[2][wave] = zl; }
+  __syncthreads();
+  se = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];     // fixed order
+  zl = ((red[2][0] + red[2][1]) + red[2][2]) + red[2][3];
+#pragma unroll
+  for (int q = 0; q < ZT; ++q) {
+    const int c = tid + kThreads * q;
+    if (c < ldc) {
+      const float d = c < n_classes ? (z[q] / se - (c == label ? 1.0f : 0.0f)) * inv_b : 0.0f;
+      if (BF16) reinterpret_cast<uint16_t*>(delta)[r * ldc + c] = f32_to_bf16_rne(d);
+      else reinterpret_cast<float*>(delta)[r * ldc + c] = d;
+    }
+  }
+  if (tid == 0) row_loss[r] = (mx + logf(se)) - zl;     // an out-of-range label selects nothing
+}
+
 // Minibatch loss of each worker: mean of its row losses, rows summed in slot order.
 __global__ void loss_mean_kernel(const float* __restrict__ row_loss, float* __restrict__ losses,
                                  int n_workers, int batch) {
@@ -199,10 +268,20 @@ hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_strid
                                long bias_gs, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
                                const int* worker_steps, int step, const GatherArgs* next, hipStream_t s) {
-  const int head_blocks = (batch + kThreads / kWave - 1) / (kThreads / kWave);
   GatherArgs ga;
   memset(&ga, 0, sizeof(ga));
   if (next != nullptr) ga = *next;
+  if (n_classes > 256 && n_classes <= 4 * kThreads && ldc <= 4 * kThreads) {   // one workgroup per row
+    dim3 grid(batch + (next != nullptr ? next->batch : 0), n_workers);
+    if (bf16)
+      hipLaunchKernelGGL(softmax_xent_row_kernel<true>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
+                         bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step, batch, ga);
+    else
+      hipLaunchKernelGGL(softmax_xent_row_kernel<false>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
+                         bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step, batch, ga);
+    return hipGetLastError();
+  }
+  const int head_blocks = (batch + kThreads / kWave - 1) / (kThreads / kWave);
   dim3 grid(head_blocks + (next != nullptr ? next->batch : 0), n_workers);
   if (bf16)
     hipLaunchKernelGGL(softmax_xent_kernel<true>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,

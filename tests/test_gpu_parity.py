@@ -175,6 +175,8 @@ MLP_SHAPES = [
     dict(dims=(64, 10), batch=8),                                # single layer (softmax regression)
     dict(dims=(33, 1), batch=4),                                 # one class: loss identically 0
     dict(dims=(20, 16, 16, 16, 16, 5), batch=1, n_workers=1),    # B = 1, N = 1, deep
+    dict(dims=(48, 40, 300), batch=9, n_workers=2),              # wide loss head: one workgroup per row
+    dict(dims=(72, 1000), batch=5, n_workers=2),                 # ... with a split logits contraction
 ]
 
 
@@ -294,6 +296,7 @@ def test_epoch_kernel_heterogeneous_steps(P, D):
     dict(dims=(96, 80, 40, 10), batch=64, n_workers=4),
     dict(dims=(100, 72, 10), batch=24, n_workers=3),
     dict(dims=(136, 264, 136, 12), batch=128, n_workers=2),
+    dict(dims=(96, 80, 520), batch=40, n_workers=3),              # wide loss head, padded to whole tiles
 ])
 @pytest.mark.parametrize("fused", [True, False])
 def test_mlp_bf16_loss_and_parameters(P, D, shape, fused):
