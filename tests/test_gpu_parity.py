@@ -454,6 +454,24 @@ def test_bf16_full_size_replicas(P, D, name, iters, interval):
     P.prsgd_destroy(h)
 
 
+@pytest.mark.parametrize("name", ["c3", "c5"])
+def test_first_layer_pass_at_full_size_matches_the_separate_launches(P, D, name):
+    # the launch shapes the benchmark times (c5: non-temporal weight traffic, 128-row minibatches;
+    # c3: 64-row minibatches, 16 replicas): fused and separate forms agree bit for bit
+    w = get_workload(name).scaled(rows_per_worker=256, iterations=5, interval=3)
+    inp = make_inputs(w)
+    outs = []
+    for on in (True, False):
+        h = _open(D, w, inp)
+        P.prsgd_set_first_layer_fusion(h, on)
+        names = _kernel_names(P, h, w.iterations, w.interval)
+        assert ("gemm_bwd_first" in names) == on, names
+        outs.append((P.prsgd_read_params(h, 0), P.prsgd_read_params(h, w.n_workers - 1), P.prsgd_read_loss(h)))
+        P.prsgd_destroy(h)
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+
+
 # --------------------------------------------------------------------------- restart average
 @pytest.mark.parametrize("n_workers", [1, 2, 3, 8, 19, 64])
 def test_restart_average_properties(P, D, n_workers):
