@@ -226,6 +226,72 @@ __global__ __launch_bounds__(kThreads) void softmax_xent_row_kernel(
   if (tid == 0) row_loss[r] = (mx + logf(se)) - zl;     // an out-of-range label selects nothing
 }
 
+// Narrow head (at most 16 classes, bf16 operands): the logits product is taken here as well,
+//   z_b = H_{L-1}[b, :] bf16(W_L) + b_L,
+// one wavefront per minibatch row with the contraction spread over its lanes -- a product of a few
+// thousand multiply-adds per row does not pay for a launch of its own (and its split contraction).
+__global__ __launch_bounds__(kThreads) void softmax_xent_narrow_kernel(
+    const uint16_t* __restrict__ h, long h_gs, int ldh, int k_dim, const uint16_t* __restrict__ w_sh,
+    long w_gs, const float* __restrict__ bias, long bias_gs, const int32_t* __restrict__ yb,
+    uint16_t* __restrict__ delta, float* __restrict__ row_loss, int batch, int n_classes, int ldc,
+    const int* __restrict__ worker_steps, int step, int head_blocks, GatherArgs next) {
+  const int g = blockIdx.y;
+  if ((int)blockIdx.x >= head_blocks) {                 // the minibatch draw of the next iteration
+    gather_row<true>(next, (int)blockIdx.x - head_blocks, g);
+    return;
+  }
+  if (worker_steps != nullptr && step >= worker_steps[g]) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.x * (kThreads / kWave) + wave;
+  if (b >= batch) return;
+  const size_t r = (size_t)g * batch + b;
+  const uint16_t* h_r = h + (size_t)g * h_gs + (size_t)b * ldh;
+  const uint16_t* w_g = w_sh + (size_t)g * w_gs;        // [k_dim][ldc], ldc = 8 or 16
+  typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+  float acc[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) acc[c] = 0.0f;
+#pragma unroll 8
+  for (int k = lane; k < k_dim; k += kWave) {
+    const float hv = bf16_to_f32(h_r[k]);
+    const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(w_g + (size_t)k * ldc);
+    u32x4_t hi = {0u, 0u, 0u, 0u};
+    if (ldc > 8) hi = *reinterpret_cast<const u32x4_t*>(w_g + (size_t)k * ldc + 8);   // uniform
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc[2 * j] = fmaf(hv, __uint_as_float(lo[j] << 16), acc[2 * j]);
+      acc[2 * j + 1] = fmaf(hv, __uint_as_float(lo[j] & 0xFFFF0000u), acc[2 * j + 1]);
+      acc[8 + 2 * j] = fmaf(hv, __uint_as_float(hi[j] << 16), acc[8 + 2 * j]);
+      acc[8 + 2 * j + 1] = fmaf(hv, __uint_as_float(hi[j] & 0xFFFF0000u), acc[8 + 2 * j + 1]);
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc[c] += __shfl_xor(acc[c], o);
+  // lane c keeps class c
+  float z = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+    if (lane == c && c < n_classes) z = acc[c] + bias[(size_t)g * bias_gs + c];
+  float mx = z;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  const int label = yb[r];
+  const float e = lane < n_classes ? expf(z - mx) : 0.0f;
+  float se = e, zl = (lane == label && lane < n_classes) ? z : 0.0f;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    se += __shfl_xor(se, o);
+    zl += __shfl_xor(zl, o);
+  }
+  if (lane < ldc) {
+    const float d = lane < n_classes ? (e / se - (lane == label ? 1.0f : 0.0f)) * (1.0f / (float)batch) : 0.0f;
+    delta[r * ldc + lane] = f32_to_bf16_rne(d);
+  }
+  if (lane == 0) row_loss[r] = (mx + logf(se)) - zl;    // an out-of-range label selects nothing
+}
+
 // Minibatch loss of each worker: mean of its row losses, rows summed in slot order.
 __global__ void loss_mean_kernel(const float* __restrict__ row_loss, float* __restrict__ losses,
                                  int n_workers, int batch) {
@@ -291,6 +357,26 @@ hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_strid
     hipLaunchKernelGGL(softmax_xent_kernel<false>, grid, dim3(kThreads), 0, s, logits, n_parts, part_stride,
                        bias, bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step,
                        head_blocks, ga);
+  return hipGetLastError();
+}
+
+bool softmax_narrow_applies(int n_classes, int ldc, bool bf16) {
+  return bf16 && n_classes >= 1 && n_classes <= 16 && (ldc == 8 || ldc == 16);
+}
+
+hipError_t launch_softmax_xent_narrow(const uint16_t* h, long h_gs, int ldh, int k_dim, const uint16_t* w_sh,
+                                      long w_gs, const float* bias, long bias_gs, const int32_t* yb,
+                                      uint16_t* delta, float* row_loss, int n_workers, int batch, int n_classes,
+                                      int ldc, const int* worker_steps, int step, const GatherArgs* next,
+                                      hipStream_t s) {
+  if (!softmax_narrow_applies(n_classes, ldc, true) || (ldh % 2) != 0) return hipErrorInvalidValue;
+  const int head_blocks = (batch + kThreads / kWave - 1) / (kThreads / kWave);
+  GatherArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  if (next != nullptr) ga = *next;
+  dim3 grid(head_blocks + (next != nullptr ? next->batch : 0), n_workers);
+  hipLaunchKernelGGL(softmax_xent_narrow_kernel, grid, dim3(kThreads), 0, s, h, h_gs, ldh, k_dim, w_sh, w_gs, bias,
+                     bias_gs, yb, delta, row_loss, batch, n_classes, ldc, worker_steps, step, head_blocks, ga);
   return hipGetLastError();
 }
 

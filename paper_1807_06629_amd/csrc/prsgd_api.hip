@@ -363,8 +363,11 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   }
   int logit_parts = 1;
   const long logit_part_stride = (long)N * B * lo.ld[L];
+  // a narrow logits layer (bf16 operands, at most 16 classes) is multiplied inside the loss-head launch
+  const bool narrow_head = softmax_narrow_applies(lo.d[L], lo.ld[L], bf16);
   for (int l = 1; l <= L; ++l) {
     if (l == 1 && h1_ready) continue;
+    if (l == L && narrow_head) continue;
     GemmArgs p = base;
     p.a = act_in(l - 1); p.a_gs = (long)B * lo.ld[l - 1]; p.lda = lo.ld[l - 1];
     p.b = bf16 ? (const void*)(reinterpret_cast<const uint16_t*>(wsrc) + lo.w_off[l - 1])
@@ -386,6 +389,15 @@ int mlp_step(prsgd_ctx* ctx, int64_t t, const int* worker_steps, int step, bool 
   const bool prefetch = worker_steps == nullptr;
   GatherArgs next_batch = batch_args(bk ^ 1, t + 1);
   if (prefetch) ctx->batch_t[bk ^ 1] = -1;
+  if (narrow_head)
+    LAUNCH(ctx, KK_LOSS,
+           launch_softmax_xent_narrow(reinterpret_cast<const uint16_t*>(act_in(L - 1)), (long)B * lo.ld[L - 1],
+                                      lo.ld[L - 1], lo.d[L - 1],
+                                      reinterpret_cast<const uint16_t*>(wsrc) + lo.w_off[L - 1], w_gs,
+                                      ctx->src() + lo.b_off[L - 1], ctx->src_stride(), ctx->yb(bk),
+                                      ctx->at<uint16_t>(cv.delta[L]), ctx->at<float>(cv.row_loss), N, B, lo.d[L],
+                                      lo.ld[L], worker_steps, step, prefetch ? &next_batch : nullptr, s));
+  else
   LAUNCH(ctx, KK_LOSS,
          launch_softmax_xent(ctx->at<float>(cv.logits), logit_parts, logit_part_stride,
                              logit_parts > 1 ? ctx->src() + lo.b_off[L - 1] : nullptr, ctx->src_stride(),

@@ -150,6 +150,13 @@ hipError_t launch_softmax_xent(const float* logits, int n_parts, long part_strid
                                long bias_gs, const int32_t* yb, void* delta, float* row_loss,
                                int n_workers, int batch, int n_classes, int ldc, bool bf16,
                                const int* worker_steps, int step, const GatherArgs* next, hipStream_t s);
+// Narrow head (<= 16 classes, bf16 operands): logits product, softmax and delta in one launch
+bool softmax_narrow_applies(int n_classes, int ldc, bool bf16);
+hipError_t launch_softmax_xent_narrow(const uint16_t* h, long h_gs, int ldh, int k_dim, const uint16_t* w_sh,
+                                      long w_gs, const float* bias, long bias_gs, const int32_t* yb,
+                                      uint16_t* delta, float* row_loss, int n_workers, int batch, int n_classes,
+                                      int ldc, const int* worker_steps, int step, const GatherArgs* next,
+                                      hipStream_t s);
 hipError_t launch_loss_mean(const float* row_loss, float* losses, int n_workers, int batch,
                             hipStream_t s);
 
