@@ -14,7 +14,9 @@
 // (B x 64) stay in registers; per tile it stages D_l[:, n-tile] and bf16(W tile) in LDS, runs both
 // products on the matrix cores (v_mfma_f32_32x32x16_bf16), passes the dW tile through LDS into the
 // row-major layout of the 16-byte weight loads, and writes master and shadow back.  Weight tiles
-// are fetched two tiles ahead, D_l tiles (L2-resident: B x d_l bf16) one tile ahead.
+// are fetched two tiles ahead, D_l tiles (L2-resident: B x d_l bf16) one tile ahead.  The
+// whole-tile variant also comes with 32-row bands, for layers whose 64-row bands would leave
+// compute units with a single workgroup and nothing to overlap its waits with.
 #include <atomic>
 
 #include "prsgd_internal.h"
@@ -299,7 +301,8 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
   }
 }
 
-// The same step for layers made of whole tiles only (B = 32 MB, d_{l-1} and d_l multiples of 64):
+// The same step for layers made of whole tiles only (B = 32 MB, d_{l-1} a multiple of the band
+// height KB = 64 or 32, d_l a multiple of 64):
 // no masks anywhere, and -- the point of the variant -- every tile step issues the same vector
 // memory instructions in the same order on every path: D-tile loads, stores of the updated
 // tile, loads of the weight tile S steps ahead.  The hardware counts outstanding memory
@@ -311,12 +314,15 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_kernel(BwdArgs p) {
 // loads and stores run once after the walk.
 constexpr int kMaxBiasTiles = 4;   // column tiles whose bias a workgroup may own in this variant
 
-template <int MB, bool DX, int S, bool MOM, bool NT>
+template <int MB, bool DX, int S, bool MOM, bool NT, int KB>
 __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
   constexpr int BR = 32 * MB;
-  constexpr int NTD = DX ? (2 * MB + 3) / 4 : 1;
+  constexpr int KH = KB / 32;                          // 32-row halves of the band
+  constexpr int QW = KB / 16;                          // 16-byte vectors of a weight tile per thread
+  constexpr int SHK = KB == 64 ? SH : 32;              // LDS row stride of the H^T panel
+  constexpr int NTD = DX ? (KH * MB + 3) / 4 : 1;
 
-  const int tiles = p.K / BMK;
+  const int tiles = p.K / KB;
   int g, tile;
   if ((p.n_groups & 7) == 0) {
     const int slot = blockIdx.x >> 3;
@@ -327,14 +333,14 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
     tile = blockIdx.x % tiles;
   }
   if (p.worker_steps != nullptr && p.step >= p.worker_steps[g]) return;
-  const int k0 = tile * BMK;
+  const int k0 = tile * KB;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* HT = reinterpret_cast<uint16_t*>(smem);            // [BR][SH]
-  uint16_t* Dl = HT + BR * SH;                                 // [BR][SD]
-  uint16_t* Wl = Dl + BR * SD;                                 // [BMK][SW]
-  float* Gl = reinterpret_cast<float*>(Wl + BMK * SW);         // [BMK][SG]
-  float* Bs = Gl + BMK * SG;                                   // [4][BN] partial column sums
+  uint16_t* HT = reinterpret_cast<uint16_t*>(smem);            // [BR][SHK]
+  uint16_t* Dl = HT + BR * SHK;                                // [BR][SD]
+  uint16_t* Wl = Dl + BR * SD;                                 // [KB][SW]
+  float* Gl = reinterpret_cast<float*>(Wl + KB * SW);          // [KB][SG]
+  float* Bs = Gl + KB * SG;                                    // [4][BN] partial column sums
   float* Bk = Bs + 4 * BN;                                     // [kMaxBiasTiles][BN] db of owned tiles
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -361,16 +367,16 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
     for (int q = 0; q < MB; ++q)
       *reinterpret_cast<u32x4_t*>(lds + (q * 32 + prow) * stride + pcol) = reg[q];
   };
-  auto fetch_w = [&](f32x4_t (&reg)[4], const float* base, int n0, bool stream) __attribute__((always_inline)) {
+  auto fetch_w = [&](f32x4_t (&reg)[QW], const float* base, int n0, bool stream) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < QW; ++q) {
       const f32x4_t* src = reinterpret_cast<const f32x4_t*>(base + (size_t)(k0 + q * 16 + wrow) * p.ldw + n0 + wcol);
       reg[q] = stream ? __builtin_nontemporal_load(src) : *src;
     }
   };
-  auto stash_w = [&](const f32x4_t (&reg)[4]) __attribute__((always_inline)) {
+  auto stash_w = [&](const f32x4_t (&reg)[QW]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < QW; ++q) {
       const u32x2_t hv = {(uint32_t)f32_to_bf16_rne(reg[q].x) | ((uint32_t)f32_to_bf16_rne(reg[q].y) << 16),
                           (uint32_t)f32_to_bf16_rne(reg[q].z) | ((uint32_t)f32_to_bf16_rne(reg[q].w) << 16)};
       *reinterpret_cast<u32x2_t*>(Wl + (q * 16 + wrow) * SW + wcol) = hv;
@@ -382,12 +388,26 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
   auto col_tile = [&](int i) { const int c = i + rot; return c >= n_t ? c - n_t : c; };
 
   u32x4_t pr[MB];
-  f32x4_t wr[S][4];
-  f32x4_t vr[MOM ? S : 1][4];
-  fetch_panel(pr, h_g, p.ldh, k0);
+  f32x4_t wr[S][QW];
+  f32x4_t vr[MOM ? S : 1][QW];
+  if constexpr (KB == 64) {
+    fetch_panel(pr, h_g, p.ldh, k0);
+  } else {                                             // a 32-wide panel: four 16-byte vectors per row
+#pragma unroll
+    for (int q = 0; q < (MB + 1) / 2; ++q)
+      if (q * 64 + (tid >> 2) < BR)
+        pr[q] = *reinterpret_cast<const u32x4_t*>(h_g + (size_t)(q * 64 + (tid >> 2)) * p.ldh + k0 + (tid & 3) * 8);
+  }
   fetch_w(wr[0], wsrc_g, col_tile(0) * BN, nt_read);
   if (MOM) fetch_w(vr[0], v_g, col_tile(0) * BN, NT);
-  stash_panel(HT, SH, pr);
+  if constexpr (KB == 64) {
+    stash_panel(HT, SHK, pr);
+  } else {
+#pragma unroll
+    for (int q = 0; q < (MB + 1) / 2; ++q)
+      if (q * 64 + (tid >> 2) < BR)
+        *reinterpret_cast<u32x4_t*>(HT + (q * 64 + (tid >> 2)) * SHK + (tid & 3) * 8) = pr[q];
+  }
   fetch_panel(pr, d_g, p.ldd, col_tile(0) * BN);
 #pragma unroll
   for (int st = 1; st < S; ++st) {
@@ -402,11 +422,13 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
     for (int v = 0; v < 16; ++v) acc_dx[t][v] = 0.0f;
 
   const int wk = wave >> 1, wn = wave & 1;
+  // wavefronts without a block of the weight-gradient tile (32-row bands) take the D_{l-1} blocks first
+  const int dxw = KB == 64 ? wave : ((wave + 2) & 3);
   int bias_slot = 0;                                   // owned bias tiles met so far (uniform)
 
   // PF: fetch the weight tile S steps ahead.  DNEXT: fetch the next D tile.
   // (the two flags are literal at every call site and fold away once the step is inlined)
-  auto tile_step = [&](int it, f32x4_t (&wr)[4], f32x4_t (&vr)[4], const bool PF, const bool DNEXT) __attribute__((always_inline)) {
+  auto tile_step = [&](int it, f32x4_t (&wr)[QW], f32x4_t (&vr)[QW], const bool PF, const bool DNEXT) __attribute__((always_inline)) {
     const int ct = col_tile(it), n0 = ct * BN;
     stash_panel(Dl, SD, pr);
     if (DX) stash_w(wr);
@@ -416,15 +438,17 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
     f32x16_t acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    if (KH == 2 || wk < KH) {
 #pragma unroll
-    for (int kk = 0; kk < BR / 16; ++kk)
-      acc = mfma_bf16(frag_trans(HT, SH, wk * 32, kk, lane), frag_trans(Dl, SD, wn * 32, kk, lane), acc);
+      for (int kk = 0; kk < BR / 16; ++kk)
+        acc = mfma_bf16(frag_trans(HT, SHK, wk * 32, kk, lane), frag_trans(Dl, SD, wn * 32, kk, lane), acc);
+    }
     if (DX) {
 #pragma unroll
       for (int t = 0; t < NTD; ++t) {
-        const int blk = wave + 4 * t;
-        if (blk < 2 * MB) {
-          const int mb = blk >> 1, kblk = blk & 1;
+        const int blk = dxw + 4 * t;
+        if (blk < KH * MB) {
+          const int mb = blk / KH, kblk = blk % KH;
 #pragma unroll
           for (int kk = 0; kk < BN / 16; ++kk)
             acc_dx[t] = mfma_bf16(frag_contig(Dl, SD, mb * 32, kk, lane),
@@ -439,14 +463,16 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
       for (int b = wave * (BR / 4); b < (wave + 1) * (BR / 4); ++b) cs += bf16_to_f32(Dl[b * SD + lane]);
       Bs[wave * BN + lane] = cs;
     }
+    if (KH == 2 || wk < KH) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v)
-      Gl[(wk * 32 + 8 * (v / 4) + 4 * kb + (v % 4)) * SG + wn * 32 + lr32] = acc[v];
+      for (int v = 0; v < 16; ++v)
+        Gl[(wk * 32 + 8 * (v / 4) + 4 * kb + (v % 4)) * SG + wn * 32 + lr32] = acc[v];
+    }
     __syncthreads();
 
     // eq. (3) on the tile, in the layout of the weight loads
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < QW; ++q) {
       const int row = q * 16 + wrow;
       f32x4_t gr = *reinterpret_cast<const f32x4_t*>(Gl + row * SG + wcol);
       const size_t off = (size_t)(k0 + row) * p.ldw + n0 + wcol;
@@ -522,14 +548,14 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
     uint16_t* dx_g = p.dx + (size_t)g * p.dx_gs;
 #pragma unroll
     for (int t = 0; t < NTD; ++t) {
-      const int blk = wave + 4 * t;
-      if (blk < 2 * MB) {
-        const int mb = blk >> 1, kblk = blk & 1;
+      const int blk = dxw + 4 * t;
+      if (blk < KH * MB) {
+        const int mb = blk / KH, kblk = blk % KH;
         const int k = k0 + kblk * 32 + lr32;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int b = mb * 32 + 8 * (v / 4) + 4 * kb + (v % 4);
-          const float hval = bf16_to_f32(HT[b * SH + kblk * 32 + lr32]);
+          const float hval = bf16_to_f32(HT[b * SHK + kblk * 32 + lr32]);
           dx_g[(size_t)b * p.lddx + k] = f32_to_bf16_rne(acc_dx[t][v] * dact_from_h(hval, p.act));
         }
       }
@@ -537,45 +563,61 @@ __global__ __launch_bounds__(kThreads) void grouped_bwd_full_kernel(BwdArgs p) {
   }
 }
 
-template <int MB, bool DX, bool MOM> hipError_t launch_bwd_full2(const BwdArgs& p, hipStream_t s);
-
 // Whether the whole-tile variant with S tiles in flight applies to the layer described by p.
-static bool bwd_full_applies(const BwdArgs& p, int mb, int S) {
-  if (p.B != 32 * mb || (p.K % BMK) != 0 || (p.Nn % BN) != 0) return false;
-  const int tiles = p.K / BMK, n_t = p.Nn / BN;
+static bool bwd_full_applies(const BwdArgs& p, int mb, int S, int kb = BMK) {
+  if (p.B != 32 * mb || (p.K % kb) != 0 || (p.Nn % BN) != 0) return false;
+  const int tiles = p.K / kb, n_t = p.Nn / BN;
   if (n_t < 2 * S || (n_t % S) != 0) return false;
   if ((n_t + tiles - 1) / tiles > kMaxBiasTiles) return false;
   // 16-byte vectors: every row of the operands must start 16-byte aligned
   return (p.ldw % 4) == 0 && (p.ldh % 8) == 0 && (p.ldd % 8) == 0 && (p.w_off % 4) == 0;
 }
 
-template <int MB, bool DX, bool MOM, int S>
+// Fewer than two workgroups of 64-row bands per compute unit on the current device.
+static bool few_bands(const BwdArgs& p) {
+  static std::atomic<int> cus{0};
+  int n = cus.load(std::memory_order_relaxed);
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      return false;
+    cus.store(n, std::memory_order_relaxed);
+  }
+  return (long)((p.K + BMK - 1) / BMK) * p.n_groups < 2L * n;
+}
+
+template <int MB, bool DX, bool MOM, int S, int KB>
 hipError_t launch_bwd_full_s(const BwdArgs& p, hipStream_t s) {
   constexpr int BR = 32 * MB;
-  constexpr size_t kLds = sizeof(uint16_t) * (BR * SH + BR * SD + BMK * SW) +
-                          sizeof(float) * (BMK * SG + 4 * BN + kMaxBiasTiles * BN);
-  const int tiles = p.K / BMK;
+  constexpr int SHK = KB == 64 ? SH : 32;
+  constexpr size_t kLds = sizeof(uint16_t) * (BR * SHK + BR * SD + KB * SW) +
+                          sizeof(float) * (KB * SG + 4 * BN + kMaxBiasTiles * BN);
+  const int tiles = p.K / KB;
   static std::atomic<bool> configured{false};
   if (!configured.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_bwd_full_kernel<MB, DX, S, MOM, true>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_bwd_full_kernel<MB, DX, S, MOM, true, KB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_bwd_full_kernel<MB, DX, S, MOM, false>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_bwd_full_kernel<MB, DX, S, MOM, false, KB>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
     if (e != hipSuccess) return e;
     configured.store(true, std::memory_order_release);
   }
   if (p.streaming)
-    hipLaunchKernelGGL((grouped_bwd_full_kernel<MB, DX, S, MOM, true>), dim3((unsigned)(tiles * p.n_groups)),
+    hipLaunchKernelGGL((grouped_bwd_full_kernel<MB, DX, S, MOM, true, KB>), dim3((unsigned)(tiles * p.n_groups)),
                        dim3(kThreads), kLds, s, p);
   else
-    hipLaunchKernelGGL((grouped_bwd_full_kernel<MB, DX, S, MOM, false>), dim3((unsigned)(tiles * p.n_groups)),
+    hipLaunchKernelGGL((grouped_bwd_full_kernel<MB, DX, S, MOM, false, KB>), dim3((unsigned)(tiles * p.n_groups)),
                        dim3(kThreads), kLds, s, p);
   return hipGetLastError();
 }
 
 template <int MB, bool DX, bool MOM> hipError_t launch_bwd_full2(const BwdArgs& p, hipStream_t s) {
-  return launch_bwd_full_s<MB, DX, MOM, 2>(p, s);
+  return launch_bwd_full_s<MB, DX, MOM, 2, 64>(p, s);
+}
+template <int MB, bool DX, bool MOM> hipError_t launch_bwd_full2_half(const BwdArgs& p, hipStream_t s) {
+  return launch_bwd_full_s<MB, DX, MOM, 2, 32>(p, s);
 }
 
 template <int MB, bool DX, bool MOM>
@@ -621,6 +663,9 @@ hipError_t launch_bwd_fused(const BwdArgs& p, hipStream_t s) {
   // Two weight tiles in flight.  Four (possible without the backward-data product) measured
   // 272 us against 298 us on 4096 x 4096 when the kernel runs alone in a loop, but 297 us against
   // 283 us inside the real step: not kept.
+  // A layer whose 64-row bands leave compute units without a second workgroup to overlap with is
+  // walked in 32-row bands instead (twice the workgroups, each with half the rows of a tile).
+  if (few_bands(p) && bwd_full_applies(p, mb, 2, 32)) PRSGD_BWD_PICK(launch_bwd_full2_half);
   if (bwd_full_applies(p, mb, 2)) PRSGD_BWD_PICK(launch_bwd_full2);
   // A layer whose rows are padded to whole column tiles (ld a multiple of 64, less than one tile of
   // padding) is walked over its padded width: the padding columns of W_l, D_l and b_l are zero,

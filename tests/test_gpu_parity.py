@@ -406,6 +406,42 @@ def test_bf16_heterogeneous_steps_mask_the_fused_backward_kernel(P, D):
     P.prsgd_destroy(h)
 
 
+@pytest.mark.parametrize("shape", [
+    dict(dims=(72, 96, 256, 10), batch=32, n_workers=3),          # layer 2: three 32-row bands
+    dict(dims=(64, 160, 384, 12), batch=64, n_workers=2),         # five bands, six column tiles
+    dict(dims=(80, 64, 256, 256, 10), batch=128, n_workers=2),    # layers 2 and 3
+])
+@pytest.mark.parametrize("activation,momentum", [("relu", 0.0), ("tanh", 0.0), ("relu", 0.9)])
+def test_backward_kernel_on_whole_tile_layers_with_few_row_bands(P, D, shape, activation, momentum):
+    """Hidden layers made of whole 32 x 64 tiles, too small to give every compute unit two 64-row
+    bands: the backward kernel walks them in 32-row bands.  One step, a run with restarts and an
+    Algorithm 3 epoch against the oracle."""
+    w = small_mlp(gemm_dtype="bf16", activation=activation, rows_per_worker=256, interval=3, iterations=7,
+                  momentum=momentum, **shape)
+    inp = inputs_for(w)
+    kw = dict(momentum=momentum) if momentum else {}
+    h = _open(D, w, inp)
+    P.prsgd_set_restart_fusion(h, False)
+    P.prsgd_local_steps(h, 1)
+    one = oracle_run(w, inp, iterations=1, **kw)
+    assert np.allclose(P.prsgd_read_loss(h), one["losses"], rtol=BF16_LOSS_TOL)
+    assert rel_err(D.read_all(h), one["x"]) <= 1e-4
+    P.prsgd_run(h, w.iterations - 1, w.interval)
+    want = oracle_run(w, inp, **kw)
+    assert _bf16_loss_ok(P.prsgd_read_loss(h), want["losses"])
+    assert rel_err(D.read_all(h), want["x"]) <= (5e-3 if momentum == 0.0 else 2e-2)
+    P.prsgd_destroy(h)
+    if momentum == 0.0:
+        steps = [2, 0, 1][:w.n_workers]
+        h = _open(D, w, inp)
+        D.run_algorithm3(h, steps, 2)
+        args = oracle_args(w, inp)
+        want = oracle.run_heterogeneous(**args, lr=w.lr, worker_steps=steps, n_epochs=2)
+        assert P.prsgd_iteration(h) == want["t"]
+        assert rel_err(D.read_all(h), want["x"]) <= 5e-3
+        P.prsgd_destroy(h)
+
+
 # --------------------------------------------------------------------------- full-size shapes, as benchmarked
 def test_c2_full_horizon(P, D):
     # the benchmark's default workload at its full T = 2000, I = 16 (epoch kernel, 125 restarts)
