@@ -229,6 +229,9 @@ EPOCH_SHAPES = [
     dict(dims=(100, 48, 7), batch=20, n_workers=8),                # ragged d0 (7 row blocks), two batch tiles
     dict(dims=(256, 128, 10), batch=8, n_workers=16),              # C4's shape
     dict(dims=(784, 256, 10), batch=32, n_workers=8),              # C2's shape
+    dict(dims=(784, 256, 10), batch=32, n_workers=16),             # one workgroup on every compute unit
+    dict(dims=(600, 48, 7), batch=20, n_workers=3),                # ragged last row block of 38
+    dict(dims=(900, 32, 33), batch=30, n_workers=2),               # 57 row blocks: eight per wavefront; 33 classes
     dict(dims=(128, 64, 33), batch=50, n_workers=2),               # 33 classes (padded to 48), four batch tiles
     dict(dims=(1024, 16, 3), batch=1, n_workers=1),                # widest input, B = 1, single-member team
 ]
@@ -277,8 +280,9 @@ def test_epoch_kernel_matches_layerwise_kernels(P, D):
     assert rel_err(outs[0], outs[1]) <= 1e-5
 
 
-def test_epoch_kernel_heterogeneous_steps(P, D):
-    w = small_mlp(dims=(64, 32, 10), batch=8, n_workers=4, rows_per_worker=128)
+@pytest.mark.parametrize("dims", [(64, 32, 10), (640, 32, 10)])     # with and without minibatch prefetch
+def test_epoch_kernel_heterogeneous_steps(P, D, dims):
+    w = small_mlp(dims=dims, batch=8, n_workers=4, rows_per_worker=128)
     inp = inputs_for(w)
     steps = [5, 3, 0, 1]
     h = _open(D, w, inp)
@@ -578,6 +582,7 @@ def test_eager_average_at_full_replica_sets(P, D, name):
 LAZY_CASES = [
     ("lsq", dict()),
     ("epoch", dict(dims=(64, 32, 10), batch=8, n_workers=3)),
+    ("epoch-wide", dict(dims=(784, 32, 10), batch=16, n_workers=3)),     # seven row blocks per wavefront
     ("bf16", dict(dims=(100, 72, 40, 10), batch=24, n_workers=4, gemm_dtype="bf16", activation="relu")),
     ("fp32-layers", dict(dims=(40, 24, 16, 6), batch=6, n_workers=3)),   # no deferred broadcast: falls back
 ]
@@ -940,10 +945,11 @@ def test_argument_errors_leave_the_context_usable(P, D):
 
 
 # --------------------------------------------------------------------------- epoch kernel: the give-up path
-def test_epoch_kernel_give_up_is_reported_and_the_context_falls_back(P, D):
-    # Driven from the host: with a wait limit of zero polls the first team member to reach the
-    # team barrier gives up at once.  Every kernel still runs to its end.
-    w = small_mlp(dims=(64, 32, 10), batch=8, n_workers=8, rows_per_worker=128, interval=4, iterations=10,
+@pytest.mark.parametrize("dims", [(64, 32, 10), (640, 32, 10)])
+def test_epoch_kernel_give_up_is_reported_and_the_context_falls_back(P, D, dims):
+    # Driven from the host: with a wait limit of zero polls the first team member to reach a
+    # barrier gives up at once.  Every kernel still runs to its end.
+    w = small_mlp(dims=dims, batch=8, n_workers=8, rows_per_worker=128, interval=4, iterations=10,
                   activation="tanh")
     inp = inputs_for(w)
     h = _open(D, w, inp)
