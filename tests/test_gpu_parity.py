@@ -947,8 +947,9 @@ def test_argument_errors_leave_the_context_usable(P, D):
 # --------------------------------------------------------------------------- epoch kernel: the give-up path
 def test_epoch_kernel_give_up_is_reported_and_the_context_falls_back(P, D):
     # Driven from the host: with a wait limit of zero polls the first team member to reach the
-    # team barrier gives up at once.  Every kernel still runs to its end.
-    w = small_mlp(dims=(64, 32, 10), batch=8, n_workers=8, rows_per_worker=128, interval=4, iterations=10,
+    # team barrier gives up at once (eight members per team: they never all arrive before the first
+    # one's first poll).  Every kernel still runs to its end.
+    w = small_mlp(dims=(64, 128, 10), batch=8, n_workers=8, rows_per_worker=128, interval=4, iterations=10,
                   activation="tanh")
     inp = inputs_for(w)
     h = _open(D, w, inp)
